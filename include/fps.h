@@ -1,0 +1,167 @@
+/*
+ * libfps -- FP8 3D sliding-tile attention (forward) for AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of FPSAttention (arXiv 2506.04648): 3D bi-directional attention over the
+ * T x H x W token grid of a video latent in which Q, K, V are quantised to FP8 E4M3 with one scale
+ * per 3D token tile (Sec. 3.2, Eq. 4-5) and every query tile attends only to the key tiles of a 3D
+ * sliding tile window (Sec. 3.1, Eq. 2-3), with the (precision, window) pair optionally chosen per
+ * denoising step (Sec. 3.3, Eq. 6; Algorithm 1).
+ *
+ * Conventions that hold for every entry point unless stated otherwise
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library allocates no device memory and keeps no state between calls
+ *     other than a thread-local error string.
+ *   - Device work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and the call returns without synchronising.
+ *   - The return value is an fps_status; on failure fps_last_error() describes it.  Arguments are
+ *     validated on the host before anything is launched.  No C++ exception crosses this boundary.
+ *   - Every device tensor must be 16-byte aligned.  Inputs are never modified.
+ *   - B and heads are interchangeable for the kernels: tensors are indexed by bh = b*heads + h.
+ *
+ * Token order.  A "raster" tensor is [B, heads, T, H, W, head_dim].  A "tiled" tensor is
+ * [B, heads, M*TS, head_dim]: the grid is zero-padded up to multiples of the tile (Tt,Th,Tw), the
+ * tile grid is (nT,nH,nW) = ceil((T,H,W)/(Tt,Th,Tw)), M = nT*nH*nW, TS = Tt*Th*Tw, token (t,h,w)
+ * sits at position u*TS + r with u = ((t/Tt)*nH + h/Th)*nW + w/Tw and
+ * r = ((t%Tt)*Th + h%Th)*Tw + w%Tw (Sec. 3.2 step (1): tokens of one 3D tile are contiguous).
+ * Padded slots of tiled inputs must be zero (fps_tile_order writes them so); padded keys never
+ * contribute to any output and padded query rows are written as zero.
+ *
+ * Supported now: head_dim = 128 and TS in {32, 128}; anything else returns FPS_ERR_UNSUPPORTED.
+ */
+#ifndef FPS_H
+#define FPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FPS_OK = 0,
+    FPS_ERR_INVALID_ARG = -1,   /* null pointer, non-positive dimension, misalignment, bad enum */
+    FPS_ERR_UNSUPPORTED = -2,   /* valid request outside the implemented shapes                  */
+    FPS_ERR_WORKSPACE = -3,     /* reserved                                                      */
+    FPS_ERR_HIP = -4            /* a HIP call or kernel launch failed; text in fps_last_error()  */
+} fps_status;
+
+typedef enum {
+    FPS_PREC_BF16 = 0,   /* no quantisation: bf16 Q,K; fp16 P,V in the PV product; fp32 accumulation */
+    FPS_PREC_FP8 = 1     /* Q,K,V,P in E4M3 with per-tile scales (Sec. 3.2)                       */
+} fps_precision;
+
+typedef enum {
+    FPS_VSCALE_TILE = 0,    /* one V scale per 3D tile, like Q and K                              */
+    FPS_VSCALE_CHANNEL = 1  /* one V scale per channel over all tokens (Sec. 3.2, Alg. 1 step 3)  */
+} fps_vscale;
+
+typedef enum { FPS_ROLE_Q = 0, FPS_ROLE_K = 1, FPS_ROLE_V = 2 } fps_role;
+typedef enum { FPS_OUT_BF16 = 0, FPS_OUT_F32 = 1 } fps_out_dtype;
+
+typedef struct {
+    int B, heads, head_dim;   /* head_dim must be 128                                             */
+    int T, H, W;              /* real token grid                                                  */
+    int Tt, Th, Tw;           /* tile; the padded grid is the grid rounded up to tile multiples   */
+} fps_shape;
+
+/* Window in tiles (Eq. 2): key tile v is kept for query tile u iff |u_a - v_a| <= w_a/2 (integer
+ * division) on each axis a; ranges are truncated at the grid boundary.  An even w_a therefore
+ * keeps the same tiles as w_a + 1, and w_a >= 2*n_a - 1 keeps the whole axis (dense). */
+typedef struct { int wt, wh, ww; } fps_window;
+
+typedef struct { fps_precision prec; fps_window win; } fps_regime;
+
+/* Denoising-step-aware schedule (Eq. 6): step t in 1..num_steps, thresholds t1 = alpha1*num_steps,
+ * t2 = alpha2*num_steps evaluated in float; regime[0] if t <= t1, regime[1] if t1 < t <= t2,
+ * regime[2] otherwise.  Requires 0 < alpha1 < alpha2 < 1. */
+typedef struct {
+    int step, num_steps;
+    float alpha1, alpha2;
+    fps_regime regime[3];
+} fps_step_cfg;
+
+/* Thread-local description of the last failure on the calling thread; never NULL. */
+const char* fps_last_error(void);
+
+/* ---- host-only helpers (no device work) ------------------------------------------------- */
+
+/* Eq. 6 / Algorithm 1 step 1.  Writes the selected regime to *out. */
+int fps_schedule_select(const fps_step_cfg* cfg, fps_regime* out);
+
+/* M, the number of tiles per head, or 0 on an invalid shape. */
+size_t fps_num_tiles(const fps_shape* shape);
+
+/* Bytes of one packed tensor for the given precision (all B*heads): M*TS*head_dim bytes for FP8,
+ * twice that for BF16.  0 on an invalid shape. */
+size_t fps_packed_bytes(const fps_shape* shape, fps_precision prec);
+
+/* Host statement of the tile neighbourhood of Eq. 2: mask[u*M + v] = 1 iff key tile v is kept for
+ * query tile u.  `mask` is host memory of M*M bytes.  Also returns the number of kept pairs
+ * through *pairs_or_null (the M x |W(u)| dense blocks of Sec. 3.1). */
+int fps_tile_mask_host(const fps_shape* shape, const fps_window* win, uint8_t* mask,
+                       uint64_t* pairs_or_null);
+
+/* ---- device entry points ------------------------------------------------------------------ */
+
+/* Sec. 3.2 step (1).  raster bf16 [B,heads,T,H,W,128] (device) -> tiled bf16 [B,heads,M*TS,128]
+ * (device), padded slots written as zero. */
+int fps_tile_order(const fps_shape* shape, const void* x_raster_bf16, void* x_tiled_bf16,
+                   void* stream);
+
+/* Inverse of fps_tile_order for outputs: tiled [B,heads,M*TS,128] of dtype `dt` (device) ->
+ * raster [B,heads,T,H,W,128] of the same dtype (device). */
+int fps_tile_unorder(const fps_shape* shape, const void* o_tiled, fps_out_dtype dt, void* o_raster,
+                     void* stream);
+
+/* Eq. 4-5 (Algorithm 1 steps 2-3).  Tiled bf16 (device) -> E4M3 codes in the library's packed
+ * operand layout for `role` (device, fps_packed_bytes(shape, FPS_PREC_FP8) bytes) and fp32 scales
+ * (device): [B,heads,M] for per-tile scales, [B,heads,128] for FPS_VSCALE_CHANNEL (role V only).
+ * scale = amax/448 as a correctly rounded float division (1.0 for an all-zero group); code =
+ * round-to-nearest-even, saturating, of the exact quotient x/scale.  `vscale` is ignored for
+ * roles Q and K. */
+int fps_quantize_tiles(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
+                       fps_vscale vscale, void* xq_out, float* scales_out, void* stream);
+
+/* BF16-mode counterpart of fps_quantize_tiles: re-lays a tiled bf16 tensor (device) into the
+ * packed operand layout for `role` (device, fps_packed_bytes(shape, FPS_PREC_BF16) bytes).
+ * Q and K keep their bf16 values.  V is stored as fp16 after an exact per-tile power-of-two
+ * scaling (so that P can be held in fp16, 11 significant bits, in the PV product); the scales
+ * 2^e go to vscale_out, fp32 [B,heads,M] (device), required for role V and ignored otherwise.
+ * bf16 values more than 2^28 times smaller than their tile's largest magnitude lose precision. */
+int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
+                        void* xp_out, float* vscale_out, void* stream);
+
+/* Debug: packed E4M3 tensor (device) -> plain row-major codes [B,heads,M*TS,128] (device). */
+int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,
+                        uint8_t* codes_rowmajor, void* stream);
+
+/* Debug: the raw score accumulators sum_c qcode_ic * kcode_jc (before the s^Q s^K / sqrt(d)
+ * dequantisation of Eq. 3) of query tile u and key tile v of head bh, computed with the same
+ * matrix instruction as fps_attn_fwd; `scores` is device memory of TS*TS floats, [query][key]
+ * in in-tile rank order.  Used to measure the accumulation accuracy of the hardware. */
+int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u, int v,
+                        float* scores, void* stream);
+
+/* Eq. 2-3 and Sec. 3.2 "aggregation and dequantisation" (Algorithm 1 steps 4-5).
+ *   q, k, v    packed tensors (device) made by fps_quantize_tiles (FP8) or fps_pack_tiles_bf16
+ *              (BF16) with roles Q, K, V for the same shape.
+ *   sq, sk, sv fp32 scales (device) from fps_quantize_tiles; in BF16 mode sq and sk are ignored
+ *              (may be NULL) and sv is the vscale_out of fps_pack_tiles_bf16.
+ *   step       if non-NULL, (prec, win) are replaced by fps_schedule_select(step); the packed
+ *              tensors must match the selected precision.
+ *   out        tiled [B,heads,M*TS,128] of dtype out_dt (device); padded query rows get 0.
+ *   visited    NULL, or device memory of M*M bytes zeroed by the caller: the kernel sets
+ *              visited[u*M+v] = 1 for every tile pair it computes (written by head 0 only).
+ * Scores are dequantised per tile pair (s^Q_u * s^K_v / sqrt(d)); softmax runs online in base 2
+ * with an integer row reference; P is rounded to E4M3 after scaling by 448 (FP8) or to fp16
+ * (BF16); the denominator sums the unrounded P. */
+int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision prec,
+                 const fps_step_cfg* step, const void* q, const void* k, const void* v,
+                 const float* sq, const float* sk, const float* sv, fps_vscale vscale, void* out,
+                 fps_out_dtype out_dt, uint8_t* visited, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FPS_H */

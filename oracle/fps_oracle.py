@@ -203,14 +203,15 @@ def schedule_select(step: int, num_steps: int, alpha1: float, alpha2: float) -> 
 # Steps 4b-5: masked softmax attention with FP8 operands
 # ----------------------------------------------------------------------------------------------
 def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vscale=VSCALE_TILE,
-              q_tiles=None, with_slack=False, tau=2.0 ** -14):
+              q_tiles=None, return_parts=False):
     """Attention output for ONE head.
 
     q_tiled, k_tiled, v_tiled: float64 (or float32) [M*TS, d], tile-ordered, zero padded.
     Returns O float64 [len(q_tiles)*TS, d] for the requested query tiles (default all), rows of
-    padded query slots being 0.  With with_slack=True also returns, per output element, the amount
-    by which a one-code change of every P element whose rounding is decided by less than the
-    relative margin tau could move that output (zero in BF16 mode).
+    padded query slots being 0.  With return_parts=True also returns, per requested query tile, the
+    intermediate quantities (key columns, dequantised scores S', row reference m, un-normalised P,
+    denominator l, quantised P, dequantised V rows, raw code dot products and the per-pair score
+    scale) so that a comparator can inspect individual rounding decisions.
     """
     M, TS = g.M, g.TS
     d = q_tiled.shape[-1]
@@ -239,32 +240,31 @@ def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vsc
         sk = np.ones(M)
 
     out = np.zeros((len(q_tiles) * TS, d), dtype=np.float64)
-    slack = np.zeros_like(out) if with_slack else None
+    parts = []
     for n, u in enumerate(q_tiles):
         vs = np.flatnonzero(keep[u])
         cols = (vs[:, None] * TS + np.arange(TS)[None, :]).reshape(-1)
         cols = cols[valid[cols]]                              # padded keys never take part
         Qu = qh[u * TS:(u + 1) * TS]
         Kw = kh[cols]
-        col_scale = sk[cols // TS]
         # S' = (q.k) * s^Q_u * s^K_v * log2(e)/sqrt(d): scores dequantised per tile pair, base 2
-        S = (Qu @ Kw.T) * (sq[u] * col_scale * c_scale)[None, :]
+        raw = Qu @ Kw.T
+        pair_scale = (sq[u] * sk[cols // TS] * c_scale)[None, :]
+        S = raw * pair_scale
         m = np.ceil(S.max(axis=1))                            # integer row reference
         p = np.exp2(S - m[:, None])                           # un-normalised P in (0, 1]
         l = p.sum(axis=1)                                     # denominator: un-quantised P
         if prec == PREC_FP8:
-            y = e4m3.FP8_MAX * p
-            ph = e4m3.round_to_e4m3(y) / e4m3.FP8_MAX         # fixed scale 1/448 (Sec. 3.2)
+            ph = e4m3.round_to_e4m3(e4m3.FP8_MAX * p) / e4m3.FP8_MAX   # fixed scale 1/448 (Sec. 3.2)
         else:
             ph = p
         o = (ph @ vh[cols]) / l[:, None]
         rows_valid = valid[u * TS:(u + 1) * TS]
         o[~rows_valid] = 0.0
         out[n * TS:(n + 1) * TS] = o
-        if with_slack and prec == PREC_FP8:
-            sl = ((e4m3.rounding_slack(y, tau) / e4m3.FP8_MAX) @ np.abs(vh[cols])) / l[:, None]
-            sl[~rows_valid] = 0.0
-            slack[n * TS:(n + 1) * TS] = sl
-    if with_slack:
-        return out, slack
+        if return_parts:
+            parts.append(dict(u=u, key_tiles=vs, cols=cols, raw=raw, pair_scale=pair_scale, S=S, m=m,
+                              p=p, l=l, ph=ph, v=vh[cols], rows_valid=rows_valid))
+    if return_parts:
+        return out, parts
     return out

@@ -1,0 +1,259 @@
+// Host side of libfps: argument validation, error text, the step-aware schedule (Eq. 6), the host
+// statement of the tile neighbourhood (Eq. 2), and the extern "C" entry points that forward to
+// the kernel launchers.
+#include "fps_internal.h"
+
+#include <stdio.h>
+#include <string.h>
+
+namespace fps {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return FPS_ERR_HIP;
+}
+
+int check_ptr(const void* p, const char* name) {
+    if (!p) { set_error("%s is NULL", name); return FPS_ERR_INVALID_ARG; }
+    if (reinterpret_cast<uintptr_t>(p) & 15u) {
+        set_error("%s is not 16-byte aligned", name);
+        return FPS_ERR_INVALID_ARG;
+    }
+    return FPS_OK;
+}
+
+int check_shape(const fps_shape* s, Geom* g) {
+    if (!s) { set_error("shape is NULL"); return FPS_ERR_INVALID_ARG; }
+    if (s->B <= 0 || s->heads <= 0 || s->T <= 0 || s->H <= 0 || s->W <= 0 || s->Tt <= 0 ||
+        s->Th <= 0 || s->Tw <= 0 || s->head_dim <= 0) {
+        set_error("shape has a non-positive dimension");
+        return FPS_ERR_INVALID_ARG;
+    }
+    const long long bh = (long long)s->B * s->heads;
+    const long long ts = (long long)s->Tt * s->Th * s->Tw;
+    const int nT = (s->T + s->Tt - 1) / s->Tt, nH = (s->H + s->Th - 1) / s->Th,
+              nW = (s->W + s->Tw - 1) / s->Tw;
+    const long long m = (long long)nT * nH * nW;
+    if (bh > (1 << 20) || m > (1 << 20) || ts > (1 << 20) || bh * m > (1LL << 28)) {
+        set_error("shape too large (B*heads*M must stay below 2^28)");
+        return FPS_ERR_INVALID_ARG;
+    }
+    if (s->head_dim != kHeadDim) {
+        set_error("head_dim %d unsupported (only 128)", s->head_dim);
+        return FPS_ERR_UNSUPPORTED;
+    }
+    if (ts != 32 && ts != 128) {
+        set_error("tile of %lld tokens unsupported (only 32 or 128)", ts);
+        return FPS_ERR_UNSUPPORTED;
+    }
+    if (!g) return FPS_OK;
+    g->BH = (int)bh;
+    g->T = s->T; g->H = s->H; g->W = s->W;
+    g->Tt = s->Tt; g->Th = s->Th; g->Tw = s->Tw;
+    g->nT = nT; g->nH = nH; g->nW = nW;
+    g->M = (int)m; g->TS = (int)ts;
+    const int lim_t[2] = {s->Tt, s->T - (nT - 1) * s->Tt};
+    const int lim_h[2] = {s->Th, s->H - (nH - 1) * s->Th};
+    const int lim_w[2] = {s->Tw, s->W - (nW - 1) * s->Tw};
+    for (int c = 0; c < 8; ++c) {
+        for (int w = 0; w < 4; ++w) g->valid_mask[c][w] = 0;
+        const int lt = lim_t[(c >> 2) & 1], lh = lim_h[(c >> 1) & 1], lw = lim_w[c & 1];
+        for (int r = 0; r < (int)ts; ++r) {
+            const int rw = r % s->Tw, rh = (r / s->Tw) % s->Th, rt = r / (s->Tw * s->Th);
+            if (rt < lt && rh < lh && rw < lw) g->valid_mask[c][r >> 5] |= 1u << (r & 31);
+        }
+    }
+    return FPS_OK;
+}
+
+static int check_window(const fps_window* w) {
+    if (!w) { set_error("window is NULL"); return FPS_ERR_INVALID_ARG; }
+    if (w->wt <= 0 || w->wh <= 0 || w->ww <= 0) {
+        set_error("window sizes must be positive");
+        return FPS_ERR_INVALID_ARG;
+    }
+    return FPS_OK;
+}
+
+static int check_enum(int v, int hi, const char* name) {
+    if (v < 0 || v > hi) { set_error("%s has invalid value %d", name, v); return FPS_ERR_INVALID_ARG; }
+    return FPS_OK;
+}
+
+}  // namespace fps
+
+using namespace fps;
+
+#define FPS_TRY(expr) do { int _rc = (expr); if (_rc != FPS_OK) return _rc; } while (0)
+
+extern "C" {
+
+const char* fps_last_error(void) { return g_err; }
+
+int fps_schedule_select(const fps_step_cfg* cfg, fps_regime* out) {
+    if (!cfg || !out) { set_error("cfg or out is NULL"); return FPS_ERR_INVALID_ARG; }
+    if (cfg->num_steps <= 0 || cfg->step < 1 || cfg->step > cfg->num_steps) {
+        set_error("step %d outside 1..%d", cfg->step, cfg->num_steps);
+        return FPS_ERR_INVALID_ARG;
+    }
+    if (!(cfg->alpha1 > 0.f && cfg->alpha1 < cfg->alpha2 && cfg->alpha2 < 1.f)) {
+        set_error("need 0 < alpha1 < alpha2 < 1");
+        return FPS_ERR_INVALID_ARG;
+    }
+    for (int i = 0; i < 3; ++i) {
+        FPS_TRY(check_enum(cfg->regime[i].prec, FPS_PREC_FP8, "regime.prec"));
+        FPS_TRY(check_window(&cfg->regime[i].win));
+    }
+    const float t1 = cfg->alpha1 * (float)cfg->num_steps;
+    const float t2 = cfg->alpha2 * (float)cfg->num_steps;
+    const float t = (float)cfg->step;
+    *out = cfg->regime[t <= t1 ? 0 : (t <= t2 ? 1 : 2)];
+    return FPS_OK;
+}
+
+size_t fps_num_tiles(const fps_shape* shape) {
+    Geom g;
+    if (check_shape(shape, &g) != FPS_OK) return 0;
+    return (size_t)g.M;
+}
+
+size_t fps_packed_bytes(const fps_shape* shape, fps_precision prec) {
+    Geom g;
+    if (check_shape(shape, &g) != FPS_OK) return 0;
+    if (check_enum(prec, FPS_PREC_FP8, "prec") != FPS_OK) return 0;
+    const size_t n = (size_t)g.BH * g.M * g.TS * kHeadDim;
+    return prec == FPS_PREC_FP8 ? n : 2 * n;
+}
+
+int fps_tile_mask_host(const fps_shape* shape, const fps_window* win, uint8_t* mask,
+                       uint64_t* pairs_or_null) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_window(win));
+    if (!mask) { set_error("mask is NULL"); return FPS_ERR_INVALID_ARG; }
+    const int rt = win->wt / 2, rh = win->wh / 2, rw = win->ww / 2;
+    uint64_t pairs = 0;
+    for (int u = 0; u < g.M; ++u) {
+        const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
+        for (int v = 0; v < g.M; ++v) {
+            const int vw = v % g.nW, vh = (v / g.nW) % g.nH, vt = v / (g.nW * g.nH);
+            const int dt = ut > vt ? ut - vt : vt - ut;
+            const int dh = uh > vh ? uh - vh : vh - uh;
+            const int dw = uw > vw ? uw - vw : vw - uw;
+            const uint8_t keep = (dt <= rt && dh <= rh && dw <= rw) ? 1 : 0;
+            mask[(size_t)u * g.M + v] = keep;
+            pairs += keep;
+        }
+    }
+    if (pairs_or_null) *pairs_or_null = pairs;
+    return FPS_OK;
+}
+
+int fps_tile_order(const fps_shape* shape, const void* x_raster_bf16, void* x_tiled_bf16,
+                   void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_ptr(x_raster_bf16, "x_raster_bf16"));
+    FPS_TRY(check_ptr(x_tiled_bf16, "x_tiled_bf16"));
+    return launch_tile_order(g, x_raster_bf16, x_tiled_bf16, (hipStream_t)stream);
+}
+
+int fps_tile_unorder(const fps_shape* shape, const void* o_tiled, fps_out_dtype dt, void* o_raster,
+                     void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_enum(dt, FPS_OUT_F32, "dt"));
+    FPS_TRY(check_ptr(o_tiled, "o_tiled"));
+    FPS_TRY(check_ptr(o_raster, "o_raster"));
+    return launch_tile_unorder(g, o_tiled, dt == FPS_OUT_F32 ? 4 : 2, o_raster,
+                               (hipStream_t)stream);
+}
+
+int fps_quantize_tiles(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
+                       fps_vscale vscale, void* xq_out, float* scales_out, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_enum(role, FPS_ROLE_V, "role"));
+    FPS_TRY(check_enum(vscale, FPS_VSCALE_CHANNEL, "vscale"));
+    FPS_TRY(check_ptr(x_tiled_bf16, "x_tiled_bf16"));
+    FPS_TRY(check_ptr(xq_out, "xq_out"));
+    FPS_TRY(check_ptr(scales_out, "scales_out"));
+    const int vs = role == FPS_ROLE_V ? (int)vscale : (int)FPS_VSCALE_TILE;
+    return launch_quantize(g, x_tiled_bf16, role, vs, xq_out, scales_out, (hipStream_t)stream);
+}
+
+int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
+                        void* xp_out, float* vscale_out, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_enum(role, FPS_ROLE_V, "role"));
+    FPS_TRY(check_ptr(x_tiled_bf16, "x_tiled_bf16"));
+    FPS_TRY(check_ptr(xp_out, "xp_out"));
+    if (role == FPS_ROLE_V) FPS_TRY(check_ptr(vscale_out, "vscale_out"));
+    return launch_pack_bf16(g, x_tiled_bf16, role, xp_out, vscale_out, (hipStream_t)stream);
+}
+
+int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,
+                        uint8_t* codes_rowmajor, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_enum(role, FPS_ROLE_V, "role"));
+    FPS_TRY(check_ptr(xq, "xq"));
+    FPS_TRY(check_ptr(codes_rowmajor, "codes_rowmajor"));
+    return launch_unpack_q8(g, xq, role, codes_rowmajor, (hipStream_t)stream);
+}
+
+int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u, int v,
+                        float* scores, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_ptr(q, "q"));
+    FPS_TRY(check_ptr(k, "k"));
+    FPS_TRY(check_ptr(scores, "scores"));
+    if (bh < 0 || bh >= g.BH || u < 0 || u >= g.M || v < 0 || v >= g.M) {
+        set_error("bh/u/v out of range");
+        return FPS_ERR_INVALID_ARG;
+    }
+    return launch_scores_fp8(g, q, k, bh, u, v, scores, (hipStream_t)stream);
+}
+
+int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision prec,
+                 const fps_step_cfg* step, const void* q, const void* k, const void* v,
+                 const float* sq, const float* sk, const float* sv, fps_vscale vscale, void* out,
+                 fps_out_dtype out_dt, uint8_t* visited, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    fps_regime sel;
+    if (step) {
+        FPS_TRY(fps_schedule_select(step, &sel));
+    } else {
+        FPS_TRY(check_window(win));
+        FPS_TRY(check_enum(prec, FPS_PREC_FP8, "prec"));
+        sel.prec = prec;
+        sel.win = *win;
+    }
+    FPS_TRY(check_enum(vscale, FPS_VSCALE_CHANNEL, "vscale"));
+    FPS_TRY(check_enum(out_dt, FPS_OUT_F32, "out_dt"));
+    FPS_TRY(check_ptr(q, "q"));
+    FPS_TRY(check_ptr(k, "k"));
+    FPS_TRY(check_ptr(v, "v"));
+    FPS_TRY(check_ptr(out, "out"));
+    if (sel.prec == FPS_PREC_FP8) {
+        FPS_TRY(check_ptr(sq, "sq"));
+        FPS_TRY(check_ptr(sk, "sk"));
+    }
+    FPS_TRY(check_ptr(sv, "sv"));
+    return launch_attn(g, sel.win, sel.prec, q, k, v, sq, sk, sv, vscale, out,
+                       out_dt == FPS_OUT_F32, visited, (hipStream_t)stream);
+}
+
+}  // extern "C"

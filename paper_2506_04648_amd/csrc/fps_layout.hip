@@ -1,0 +1,189 @@
+// Layout kernels of libfps: raster <-> tile order (Sec. 3.2 step (1)), the BF16 operand packing,
+// and the debug unpacking of packed E4M3 tensors.  All of them are pure data movement.
+//
+// Packed operand layouts, per (bh, tile) block.  "lane" = 16*g + n is the MFMA lane that consumes
+// the chunk: n selects the row of the 16-row operand block, g the group of contraction slots.
+//   E4M3 Q : row-major [token][128]                                    (TS*128 bytes)
+//   E4M3 K : 16-byte chunk ((b*2 + h)*64 + lane) = K[16b + n][32g + 16h + 0..15]
+//   E4M3 V : TS=128: 16-byte chunk ((cb*2 + h)*64 + lane), byte j -> slot s = 16h + j
+//            TS=32 :  8-byte chunk (cb*64 + lane),          byte j -> slot s = j
+//            holding V[key(g,s)][16cb + n] with key(g,s) = 16*(s/4) + 4g + s%4
+//   BF16 Q : row-major [token][128]                                    (TS*256 bytes)
+//   BF16 K : 16-byte chunk ((b*4 + ks)*64 + lane) = K[16b + n][32ks + 8g + 0..7]
+//   BF16 V : 16-byte chunk ((kk*8 + cb)*64 + lane), element e -> V[32kk + key(g,e)][16cb + n],
+//            stored as fp16 after an exact per-tile power-of-two scaling (see pack_bf16_kernel)
+// key(g,s) is the key that slot s of lane group g holds after a 16x16 MFMA wrote S^T = K Q^T: the
+// accumulator of lane (n,g) for key block b has keys 16b + 4g + 0..3, so P^T can be fed back as
+// the second operand of the PV product without any cross-lane movement.
+#include "fps_internal.h"
+
+namespace fps {
+
+__device__ __forceinline__ int key_of_slot(int g, int s) { return 16 * (s >> 2) + 4 * g + (s & 3); }
+
+// ---- raster -> tiled (bf16, 16-byte chunks of 8 channels) -------------------------------------
+__global__ void tile_order_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, Geom g,
+                                  long long n_chunks) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_chunks) return;
+    const int c16 = (int)(i & 15);
+    const long long pos = i >> 4;                       // bh * (M*TS) + u*TS + r
+    const int r = (int)(pos % g.TS);
+    const long long bu = pos / g.TS;
+    const int u = (int)(bu % g.M);
+    const long long bh = bu / g.M;
+    const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
+    const int rw = r % g.Tw, rh = (r / g.Tw) % g.Th, rt = r / (g.Tw * g.Th);
+    const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (t < g.T && h < g.H && w < g.W) {
+        const long long src = (((bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16 + c16;
+        val = in[src];
+    }
+    out[i] = val;
+}
+
+// ---- tiled -> raster (elem_bytes 2 or 4; 16-byte chunks) ---------------------------------------
+__global__ void tile_unorder_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, Geom g,
+                                    int chunks_per_row, long long n_chunks) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_chunks) return;
+    const int c = (int)(i % chunks_per_row);
+    long long tok = i / chunks_per_row;                 // ((bh*T + t)*H + h)*W + w
+    const int w = (int)(tok % g.W); tok /= g.W;
+    const int h = (int)(tok % g.H); tok /= g.H;
+    const int t = (int)(tok % g.T);
+    const long long bh = tok / g.T;
+    const int u = ((t / g.Tt) * g.nH + h / g.Th) * g.nW + w / g.Tw;
+    const int r = ((t % g.Tt) * g.Th + h % g.Th) * g.Tw + w % g.Tw;
+    const long long src = ((bh * g.M + u) * (long long)g.TS + r) * chunks_per_row + c;
+    out[i] = in[src];
+}
+
+// ---- BF16 operand packing -----------------------------------------------------------------------
+// One workgroup of 256 threads per (bh, tile); the tile (TS*256 bytes) is staged in LDS.
+// Q and K keep their bf16 values.  V is converted to fp16 so that the PV product can take P in
+// fp16 (11 significant bits instead of bf16's 8): each tile is first multiplied by 2^-e with
+// amax * 2^-e in [2^14, 2^15), which keeps every bf16 value exact unless it is more than 2^28
+// times smaller than the tile's largest one, and vscale[tile] = 2^e undoes it in the kernel.
+template <int TS>
+__global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict__ in,
+                                                        uint4* __restrict__ out,
+                                                        float* __restrict__ vscale, int role) {
+    __shared__ uint16_t tile[TS * 128];
+    __shared__ uint32_t red[4];
+    const long long blk = blockIdx.x;
+    const uint4* src = in + blk * (TS * 16);
+    uint4* dst = out + blk * (TS * 16);
+    constexpr int kChunks = TS * 16;
+    if (role == FPS_ROLE_Q) {
+        for (int c = threadIdx.x; c < kChunks; c += 256) dst[c] = src[c];
+        return;
+    }
+    if (role == FPS_ROLE_K) {
+        for (int c = threadIdx.x; c < kChunks; c += 256) {
+            const int j = c >> 4, c8 = c & 15;             // row, 8-channel chunk
+            const int b = j >> 4, n = j & 15, ks = c8 >> 2, gg = c8 & 3;
+            dst[(b * 4 + ks) * 64 + gg * 16 + n] = src[c];
+        }
+        return;
+    }
+    uint4* t4 = reinterpret_cast<uint4*>(tile);
+    uint32_t mb = 0;
+    for (int c = threadIdx.x; c < kChunks; c += 256) {
+        const uint4 v = src[c];
+        t4[c] = v;
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+            mb = lo > mb ? lo : mb;
+            mb = hi > mb ? hi : mb;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)mb, off);
+        mb = o > mb ? o : mb;
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mb;
+    __syncthreads();
+    mb = red[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) mb = red[i] > mb ? red[i] : mb;
+    int e = (int)(mb >> 7) - 127 - 14;                     // floor(log2(amax)) - 14
+    e = mb == 0 ? 0 : (e < -100 ? -100 : (e > 113 ? 113 : e));
+    const float down = __uint_as_float((uint32_t)(127 - e) << 23);     // 2^-e
+    if (threadIdx.x == 0) vscale[blk] = __uint_as_float((uint32_t)(127 + e) << 23);
+    for (int c = threadIdx.x; c < kChunks; c += 256) {
+        const int lane = c & 63, cb = (c >> 6) & 7, kk = c >> 9;
+        const int gg = lane >> 4, n = lane & 15;
+        union { uint4 v; _Float16 h[8]; } o;
+#pragma unroll
+        for (int el = 0; el < 8; ++el) {
+            const uint32_t bits = tile[(32 * kk + key_of_slot(gg, el)) * 128 + 16 * cb + n];
+            o.h[el] = (_Float16)(__uint_as_float(bits << 16) * down);
+        }
+        dst[c] = o.v;
+    }
+}
+
+// ---- debug unpack of E4M3 tensors ---------------------------------------------------------------
+template <int TS>
+__global__ __launch_bounds__(256) void unpack_q8_kernel(const uint8_t* __restrict__ in,
+                                                        uint8_t* __restrict__ out, int role) {
+    const long long blk = blockIdx.x;
+    const uint8_t* src = in + blk * (TS * 128);
+    uint8_t* dst = out + blk * (TS * 128);
+    for (int i = threadIdx.x; i < TS * 128; i += 256) {
+        const int j = i >> 7, c = i & 127;                 // token, channel of the row-major output
+        int off;
+        if (role == FPS_ROLE_Q) {
+            off = i;
+        } else if (role == FPS_ROLE_K) {
+            const int b = j >> 4, n = j & 15, gg = c >> 5, h = (c >> 4) & 1;
+            off = ((b * 2 + h) * 64 + gg * 16 + n) * 16 + (c & 15);
+        } else {
+            const int cb = c >> 4, n = c & 15;
+            const int gg = (j >> 2) & 3, s = 4 * (j >> 4) + (j & 3);   // inverse of key_of_slot
+            if (TS == 128) off = ((cb * 2 + (s >> 4)) * 64 + gg * 16 + n) * 16 + (s & 15);
+            else           off = (cb * 64 + gg * 16 + n) * 8 + s;
+        }
+        dst[i] = src[off];
+    }
+}
+
+static inline int grid_for(long long n, int block) { return (int)((n + block - 1) / block); }
+
+int launch_tile_order(const Geom& g, const void* in, void* out, hipStream_t st) {
+    const long long n = (long long)g.BH * g.M * g.TS * 16;
+    tile_order_kernel<<<grid_for(n, 256), 256, 0, st>>>((const uint4*)in, (uint4*)out, g, n);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "tile_order launch");
+}
+
+int launch_tile_unorder(const Geom& g, const void* in, int elem_bytes, void* out, hipStream_t st) {
+    const int cpr = kHeadDim * elem_bytes / 16;
+    const long long n = (long long)g.BH * g.T * g.H * g.W * cpr;
+    tile_unorder_kernel<<<grid_for(n, 256), 256, 0, st>>>((const uint4*)in, (uint4*)out, g, cpr, n);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "tile_unorder launch");
+}
+
+int launch_pack_bf16(const Geom& g, const void* x, int role, void* xp, float* vscale, hipStream_t st) {
+    const int blocks = g.BH * g.M;
+    if (g.TS == 128) pack_bf16_kernel<128><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role);
+    else             pack_bf16_kernel<32><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "pack_bf16 launch");
+}
+
+int launch_unpack_q8(const Geom& g, const void* xq, int role, uint8_t* out, hipStream_t st) {
+    const int blocks = g.BH * g.M;
+    if (g.TS == 128) unpack_q8_kernel<128><<<blocks, 256, 0, st>>>((const uint8_t*)xq, out, role);
+    else             unpack_q8_kernel<32><<<blocks, 256, 0, st>>>((const uint8_t*)xq, out, role);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "unpack_q8 launch");
+}
+
+}  // namespace fps

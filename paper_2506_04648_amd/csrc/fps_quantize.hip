@@ -1,0 +1,158 @@
+// Per-tile amax -> scale -> E4M3 encode (Sec. 3.2, Eq. 4-5; Algorithm 1 step 2), writing the
+// packed operand layouts described in fps_layout.hip.  One workgroup of 256 threads per
+// (bh, tile); the pass is HBM-bound (2 bytes read, 1 byte written per element).
+#include "fps_internal.h"
+
+namespace fps {
+
+__device__ __forceinline__ int key_of_slot_q(int g, int s) { return 16 * (s >> 2) + 4 * g + (s & 3); }
+
+// Quotient x/s prepared for the hardware's round-to-nearest-even conversion so that the final code
+// equals the rounding of the EXACT quotient: the correctly rounded float quotient can land exactly
+// on an E4M3 rounding midpoint although the true quotient lies beside it; the sign of the exact
+// residual x - q*s (one fma) tells on which side, and q is moved one float ulp that way.
+__device__ __forceinline__ float quotient_for_rne(float x, float s) {
+    float q = x / s;
+    uint32_t qb = __float_as_uint(q);
+    const float a = __builtin_fabsf(q);
+    bool mid;
+    if (a >= 0.015625f) {
+        mid = (qb & 0xFFFFFu) == 0x80000u;          // 3 mantissa bits kept, next bit set, rest zero
+    } else {
+        const float t = a * 1024.0f;                 // subnormal grid 2^-9: midpoints are odd * 2^-10
+        mid = (t == __builtin_floorf(t)) && (((int)t) & 1);
+    }
+    if (mid) {
+        const float r = __builtin_fmaf(-q, s, x);
+        if (r != 0.0f) {
+            const bool up = (r > 0.0f) == (q > 0.0f);
+            qb = up ? qb + 1u : qb - 1u;             // magnitude one ulp up / down
+            q = __uint_as_float(qb);
+        }
+    }
+    return __builtin_fminf(__builtin_fmaxf(q, -448.0f), 448.0f);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// 16 bf16 (two uint4) -> 16 E4M3 codes (one uint4)
+__device__ __forceinline__ uint4 encode16(const uint4& lo, const uint4& hi, float s) {
+    const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int r = 0;
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(quotient_for_rne(bf16_lo(w[2 * i]), s),
+                                            quotient_for_rne(bf16_hi(w[2 * i]), s), r, false);
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(quotient_for_rne(bf16_lo(w[2 * i + 1]), s),
+                                            quotient_for_rne(bf16_hi(w[2 * i + 1]), s), r, true);
+        o[i] = (uint32_t)r;
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+__device__ __forceinline__ uint32_t amax_bits16(const uint4& v, uint32_t m) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+        m = lo > m ? lo : m;
+        m = hi > m ? hi : m;
+    }
+    return m;
+}
+
+template <int TS>
+__global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __restrict__ x,
+                                                             uint8_t* __restrict__ xq,
+                                                             float* __restrict__ scales, int role) {
+    constexpr int U = TS / 32;                      // 32-byte units (16 channels of one token) per thread
+    __shared__ uint32_t red[4];
+    __shared__ __attribute__((aligned(16))) uint8_t stage[TS * 128];
+    const long long blk = blockIdx.x;
+    const uint4* src = x + blk * (TS * 16);
+    uint4* dst = reinterpret_cast<uint4*>(xq + blk * (TS * 128));
+    const int tid = threadIdx.x;
+
+    uint4 lo[U], hi[U];
+    uint32_t mb = 0;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const int unit = tid + 256 * i;              // token = unit >> 3, 16-channel group = unit & 7
+        lo[i] = src[2 * unit];
+        hi[i] = src[2 * unit + 1];
+        mb = amax_bits16(lo[i], mb);
+        mb = amax_bits16(hi[i], mb);
+    }
+    // |x| of bf16 values compares like the 15-bit integer pattern: integer max across the workgroup
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)mb, off);
+        mb = o > mb ? o : mb;
+    }
+    if ((tid & 63) == 0) red[tid >> 6] = mb;
+    __syncthreads();
+    mb = red[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) mb = red[i] > mb ? red[i] : mb;
+    const float amax = __uint_as_float(mb << 16);
+    const float s = (mb == 0) ? 1.0f : amax / 448.0f;    // Eq. 4 (correctly rounded division)
+    if (tid == 0) scales[blk] = s;
+
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const int unit = tid + 256 * i;
+        const uint4 codes = encode16(lo[i], hi[i], s);
+        const int j = unit >> 3, c16 = unit & 7;
+        if (role == FPS_ROLE_Q) {
+            dst[unit] = codes;
+        } else if (role == FPS_ROLE_K) {
+            const int b = j >> 4, n = j & 15, gg = c16 >> 1, h = c16 & 1;
+            dst[(b * 2 + h) * 64 + gg * 16 + n] = codes;
+        } else {
+            reinterpret_cast<uint4*>(stage)[unit] = codes;
+        }
+    }
+    if (role != FPS_ROLE_V) return;
+    __syncthreads();
+    if (TS == 128) {
+        for (int c = tid; c < TS * 8; c += 256) {
+            const int lane = c & 63, h = (c >> 6) & 1, cb = c >> 7;
+            const int gg = lane >> 4, n = lane & 15;
+            union { uint4 v; uint8_t e[16]; } o;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj)
+                o.e[jj] = stage[key_of_slot_q(gg, 16 * h + jj) * 128 + 16 * cb + n];
+            dst[c] = o.v;
+        }
+    } else {
+        uint2* dst8 = reinterpret_cast<uint2*>(dst);
+        for (int c = tid; c < TS * 16; c += 256) {
+            const int lane = c & 63, cb = c >> 6;
+            const int gg = lane >> 4, n = lane & 15;
+            union { uint2 v; uint8_t e[8]; } o;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+                o.e[jj] = stage[key_of_slot_q(gg, jj) * 128 + 16 * cb + n];
+            dst8[c] = o.v;
+        }
+    }
+}
+
+int launch_quantize(const Geom& g, const void* x, int role, int vscale, void* xq, float* scales,
+                    hipStream_t st) {
+    if (vscale != FPS_VSCALE_TILE) {
+        set_error("per-channel V scales are not implemented yet");
+        return FPS_ERR_UNSUPPORTED;
+    }
+    const int blocks = g.BH * g.M;
+    if (g.TS == 128)
+        quantize_tiles_kernel<128><<<blocks, 256, 0, st>>>((const uint4*)x, (uint8_t*)xq, scales, role);
+    else
+        quantize_tiles_kernel<32><<<blocks, 256, 0, st>>>((const uint4*)x, (uint8_t*)xq, scales, role);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "quantize_tiles launch");
+}
+
+}  // namespace fps

@@ -1,0 +1,109 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/fps.h declares, and its
+host logic (schedule, tile mask, argument validation) agrees with the oracle.  No kernel runs."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import fps_oracle as fo
+from paper_2506_04648_amd import fps
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fps.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(fps_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(fps.EXPORTS)
+    L = fps.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert fps.last_error() is not None
+
+
+def test_schedule_select_matches_oracle():
+    regimes = [(fps.PREC_BF16, (41, 11, 9)), (fps.PREC_FP8, (7, 5, 5)), (fps.PREC_FP8, (3, 3, 3))]
+    for D, a1, a2 in [(50, 0.2, 0.5), (50, 0.3, 0.7), (7, 0.34, 0.67), (3, 0.34, 0.67), (1000, 0.123, 0.9)]:
+        for t in range(1, D + 1):
+            prec, win = fps.schedule_select(fps.make_step_cfg(t, D, a1, a2, regimes))
+            want = regimes[fo.schedule_select(t, D, a1, a2)]
+            assert (prec, win) == want
+    picks = [fps.schedule_select(fps.make_step_cfg(t, 50, 0.2, 0.5, regimes))[1] for t in range(1, 51)]
+    assert picks == [(41, 11, 9)] * 10 + [(7, 5, 5)] * 15 + [(3, 3, 3)] * 25
+
+
+@pytest.mark.parametrize("bad", [dict(step=0), dict(step=51), dict(alpha1=0.6), dict(alpha2=1.0),
+                                 dict(alpha1=0.0), dict(num_steps=0)])
+def test_schedule_select_rejects_bad_config(bad):
+    kw = dict(step=1, num_steps=50, alpha1=0.2, alpha2=0.5)
+    kw.update(bad)
+    cfg = fps.make_step_cfg(kw["step"], kw["num_steps"], kw["alpha1"], kw["alpha2"],
+                            [(1, (3, 3, 3))] * 3)
+    with pytest.raises(fps.FpsError) as e:
+        fps.schedule_select(cfg)
+    assert e.value.status == fps.FPS_ERR_INVALID_ARG and len(str(e.value)) > 0
+
+
+@pytest.mark.parametrize("grid,tile,window", [
+    ((4, 16, 16), (2, 4, 4), (1, 3, 3)),
+    ((21, 30, 52), (1, 8, 16), (3, 3, 3)),
+    ((21, 45, 80), (1, 8, 16), (5, 3, 3)),
+    ((21, 45, 80), (1, 8, 16), (6, 6, 1)),
+    ((5, 9, 33), (2, 4, 4), (2, 5, 100)),
+])
+def test_tile_mask_host_matches_oracle(grid, tile, window):
+    shape = fps.make_shape(2, grid, tile)
+    g = fo.Geometry(*grid, *tile)
+    assert fps.num_tiles(shape) == g.M
+    mask, pairs = fps.tile_mask_host(shape, window)
+    want = fo.tile_mask(g, window)
+    assert np.array_equal(mask.astype(bool), want) and pairs == int(want.sum())
+    assert fps.packed_bytes(shape, fps.PREC_FP8) == 2 * g.L_padded * 128
+    assert fps.packed_bytes(shape, fps.PREC_BF16) == 4 * g.L_padded * 128
+
+
+def test_shape_validation():
+    L = fps.lib()
+    ok = fps.make_shape(2, (4, 16, 16), (2, 4, 4))
+    assert fps.num_tiles(ok) == 32
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 4, 4), head_dim=64)) == 0
+    assert "head_dim" in fps.last_error()
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (1, 4, 4))) == 0      # 16-token tiles
+    assert "unsupported" in fps.last_error()
+    assert fps.num_tiles(fps.make_shape(0, (4, 16, 16), (2, 4, 4))) == 0
+    assert L.fps_num_tiles(None) == 0
+
+
+def test_device_entry_points_validate_before_launching():
+    """Bad arguments are refused on the host: none of these calls reaches the GPU."""
+    L = fps.lib()
+    shape = fps.make_shape(2, (4, 16, 16), (2, 4, 4))
+    win = fps.Window(1, 3, 3)
+    good = ctypes.c_void_p(0x10000)          # aligned, never dereferenced by a refused call
+    odd = ctypes.c_void_p(0x10004)
+    S = ctypes.byref(shape)
+    assert L.fps_tile_order(S, None, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert "NULL" in fps.last_error()
+    assert L.fps_tile_order(S, odd, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert "aligned" in fps.last_error()
+    assert L.fps_quantize_tiles(S, good, 3, 0, good, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_quantize_tiles(S, good, 2, 5, good, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_quantize_tiles(S, good, 0, 0, good, None, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_pack_tiles_bf16(S, good, -1, good, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_pack_tiles_bf16(S, good, 2, good, None, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_debug_unpack_q8(S, good, 0, odd, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_tile_unorder(S, good, 7, good, None) == fps.FPS_ERR_INVALID_ARG
+    bad_win = fps.Window(0, 3, 3)
+    args = (good, good, good, good, good, good, 0, good, 1, None, None)
+    assert L.fps_attn_fwd(S, ctypes.byref(bad_win), 1, None, *args) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_attn_fwd(S, ctypes.byref(win), 2, None, *args) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_attn_fwd(S, None, 1, None, *args) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_attn_fwd(S, ctypes.byref(win), 1, None, good, good, good, None, good, good, 0,
+                          good, 1, None, None) == fps.FPS_ERR_INVALID_ARG      # FP8 needs scales
+    big = fps.make_shape(2, (4, 16, 16), (2, 8, 4))                             # 64-token tiles
+    assert L.fps_attn_fwd(ctypes.byref(big), ctypes.byref(win), 1, None, *args) == fps.FPS_ERR_UNSUPPORTED
+    cfg = fps.make_step_cfg(99, 50, 0.2, 0.5, [(1, (3, 3, 3))] * 3)
+    assert L.fps_attn_fwd(S, None, 1, ctypes.byref(cfg), *args) == fps.FPS_ERR_INVALID_ARG

@@ -301,13 +301,22 @@ def test_hand_sized_case_with_subnormal_p():
     assert np.max(np.abs(o[0, 0, 0] - ref)) <= 1e-14
 
 
-def test_slack_is_zero_without_near_ties_and_positive_with_one():
+def test_parts_are_consistent_with_the_output():
     g = fo.Geometry(1, 2, 4, 1, 2, 4)
     d = 8
     q, k, v = rand_qkv(61, (g.T, g.H, g.W), d, outlier=False)
-    o, slack = fo.attention(*(fo.tile_order(a, g) for a in (q, k, v)), g, (1, 1, 1),
-                            with_slack=True, tau=0.0)
-    assert slack.shape == o.shape and np.all(slack >= 0)
-    o2, slack2 = fo.attention(*(fo.tile_order(a, g) for a in (q, k, v)), g, (1, 1, 1),
-                              with_slack=True, tau=0.5)
-    assert np.array_equal(o, o2) and np.all(slack2 >= slack) and slack2.max() > 0
+    o, parts = fo.attention(*(fo.tile_order(a, g) for a in (q, k, v)), g, (1, 1, 1), return_parts=True)
+    assert len(parts) == g.M
+    pt = parts[0]
+    assert np.array_equal(o[:g.TS], (pt["ph"] @ pt["v"]) / pt["l"][:, None])
+    assert np.array_equal(pt["S"], pt["raw"] * pt["pair_scale"])
+    assert np.all(pt["p"] <= 1.0) and np.all(pt["p"].max(axis=1) > 0.5)
+    assert np.all(np.abs(pt["ph"] - pt["p"]) <= np.maximum(pt["p"] * 2.0 ** -4, 2.0 ** -10 / 448))
+
+
+def test_rounding_slack_helper():
+    y = np.array([17.0, 17.0 * (1 + 2.0 ** -16), 17.5, 2.0 ** -8, 300.0])
+    s = e4m3.rounding_slack(y, 2.0 ** -14)
+    assert s[0] == 2.0 and s[1] == 2.0 and s[2] == 0.0 and s[4] == 0.0
+    assert s[3] == 2.0 ** -10                                  # subnormal range: half a spacing
+    assert np.all(e4m3.rounding_slack(y, 0.0)[[1, 2, 4]] == 0.0)
