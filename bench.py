@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the FP8 3D sliding-tile attention hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic Wan2.1-14B 720p-shaped inputs
+already resident in HBM: raster -> tile order (Q,K,V), per-tile FP8 quantisation (Q,K,V), the
+sliding-tile attention kernel, and tile order -> raster of the output.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-dense] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
+BF16_PEAK_TFLOPS = 2500.0
+
+
+def kept_pairs(grid, tile, window):
+    n = [-(-g // t) for g, t in zip(grid, tile)]
+    total = 1
+    for na, w in zip(n, window):
+        r = min(w // 2, na - 1)
+        total *= na * (2 * r + 1) - r * (r + 1)
+    return total, n[0] * n[1] * n[2]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan14b-720p")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense BF16 / dense FP8 reference runs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the timed CPU oracle sample")
+    ap.add_argument("--cpu-qtiles", type=int, default=48)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (heads shard across GPUs without any "
+              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_04648_amd import fps, synth
+
+    fps.lib()                                            # no fallback: fail now if not built
+    w = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    shape = fps.make_shape(w.heads, w.grid, w.tile)
+    pairs, M = kept_pairs(w.grid, w.tile, w.window)
+    TS = w.tile[0] * w.tile[1] * w.tile[2]
+    flop = pairs * w.heads * 4.0 * TS * TS * w.head_dim          # QK^T and PV on computed tiles
+
+    t0 = time.time()
+    q, k, v = synth.qkv_raster(w, workers=min(16, os.cpu_count() or 1))
+    raster = [torch.from_numpy(a[None]).to(dev).to(torch.bfloat16) for a in (q, k, v)]
+    del q, k, v
+    gen_s = time.time() - t0
+
+    # persistent buffers: the timed region allocates nothing
+    L = M * TS
+    tiled = [torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+    packed = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device=dev) for _ in range(3)]
+    scales = [torch.empty((1, w.heads, M), dtype=torch.float32, device=dev) for _ in range(3)]
+    out_tiled = torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev)
+    out_raster = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.bfloat16, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(events=None):
+        if events:
+            events[0].record()
+        for i in range(3):
+            fps.tile_order(shape, raster[i], out=tiled[i])
+        if events:
+            events[1].record()
+        for i in range(3):
+            fps.quantize_tiles(shape, tiled[i], i, out=packed[i], scales=scales[i])
+        if events:
+            events[2].record()
+        fps.attn_fwd(shape, w.window, fps.PREC_FP8, packed[0], packed[1], packed[2],
+                     scales[0], scales[1], scales[2], out=out_tiled)
+        if events:
+            events[3].record()
+        fps.tile_unorder(shape, out_tiled, out=out_raster)
+        if events:
+            events[4].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    all_events = [[ev() for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(all_events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    seg = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(4)] for e in all_events])
+    order_ms, quant_ms, attn_ms, unorder_ms = (float(x) for x in seg.mean(axis=0))
+
+    result = {
+        "metric": "effective TFLOP/s + ms/call, FP8 3D sliding-tile attention, Wan-14B 720p shape",
+        "value": flop / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s (computed tile pairs, whole hot path incl. tile order + quantise)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": w.name, "heads": w.heads, "head_dim": w.head_dim, "grid": list(w.grid),
+                   "tile": list(w.tile), "window_tiles": list(w.window), "kept_tile_pairs": pairs,
+                   "tflop_per_call": flop / 1e12, "input_gen_s": round(gen_s, 1)},
+        "breakdown_ms": {"tile_order_x3": order_ms, "quantize_x3": quant_ms, "attention": attn_ms,
+                         "tile_unorder": unorder_ms},
+        "attention_tflops": flop / (attn_ms * 1e-3) / 1e12,
+        "quantize_GBps": 3.0 * 3 * w.heads * L * 128 / (quant_ms * 1e-3) / 1e9,
+        "roofline": {"bound": "mfma", "kernel": "attn_fp8_kernel", "achieved": flop / (attn_ms * 1e-3) / 1e12,
+                     "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flop / (attn_ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, "traffic": None},
+        "paper_context": {"kernel_speedup_vs_bf16_H20": 7.09, "e2e_speedup_vs_bf16_H20": 4.96},
+    }
+
+    if not args.no_dense:
+        dense_win = tuple(2 * (-(-g // t)) - 1 for g, t in zip(w.grid, w.tile))
+        dpairs, _ = kept_pairs(w.grid, w.tile, dense_win)
+        dflop = dpairs * w.heads * 4.0 * TS * TS * w.head_dim
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        p16 = [fps.pack_tiles_bf16(shape, tiled[i], i) for i in range(3)]
+        bf16_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_BF16, p16[0][0], p16[1][0], p16[2][0],
+                                             sv=p16[2][1], out=out_tiled), 2)
+        del p16
+        fp8d_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_FP8, packed[0], packed[1], packed[2],
+                                             scales[0], scales[1], scales[2], out=out_tiled), 2)
+        result["dense"] = {"window_tiles": list(dense_win), "tflop_per_call": dflop / 1e12,
+                           "bf16_ms": bf16_ms, "bf16_tflops": dflop / bf16_ms / 1e9,
+                           "bf16_frac_of_peak": dflop / bf16_ms / 1e9 / BF16_PEAK_TFLOPS,
+                           "fp8_ms": fp8d_ms, "fp8_tflops": dflop / fp8d_ms / 1e9}
+        result["speedup_vs_own_dense_bf16"] = {"attention_only": bf16_ms / attn_ms,
+                                               "with_quantize": bf16_ms / (attn_ms + quant_ms)}
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(w, args.cpu_qtiles, TS)
+
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, n_qtiles, TS):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload:
+    head 0, per-tile quantisation of all its tiles plus attention for n_qtiles evenly spaced query
+    tiles.  Reported in the metric's unit on the sample's own computed tile pairs."""
+    import numpy as np
+    from paper_2506_04648_amd import synth
+    from oracle import fps_oracle as fo
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    g = fo.Geometry(*w.grid, *w.tile)
+    q, k, v = synth.qkv_raster(w, heads=[0])
+    tiles = sorted(set(int(x) for x in np.linspace(0, g.M - 1, n_qtiles)))
+    t0 = time.perf_counter()
+    qt, kt, vt = (fo.tile_order(a[0].astype(np.float64), g) for a in (q, k, v))
+    fo.attention(qt, kt, vt, g, w.window, q_tiles=tiles)
+    secs = time.perf_counter() - t0
+    keep = fo.tile_mask(g, w.window)
+    sample_pairs = int(keep[tiles].sum())
+    sflop = sample_pairs * 4.0 * TS * TS * w.head_dim
+    return {"value": sflop / secs / 1e12, "unit": "TFLOP/s (computed tile pairs)", "cores": threads,
+            "kind": "oracle", "seconds": secs,
+            "sample": f"head 0 of {w.name}: tile order + quantise all {g.M} tiles of Q,K,V + attention "
+                      f"for {len(tiles)} of {g.M} query tiles ({sample_pairs} tile pairs); BLAS threads = "
+                      f"cores, elementwise NumPy is single-threaded"}
+
+
+if __name__ == "__main__":
+    main()

@@ -71,11 +71,21 @@ def head_tensor(config_id: int, call_index: int, tensor_id: int, head: int, grid
     return round_to_bf16(x)
 
 
-def qkv_raster(w: Workload, call_index: int = 0, heads=None):
-    """Q, K, V as float32 arrays [n_heads_selected, T, H, W, d] holding bf16 values (B = 1)."""
-    heads = range(w.heads) if heads is None else heads
-    out = []
-    for tensor_id in range(3):
-        out.append(np.stack([head_tensor(w.config_id, call_index, tensor_id, h, w.grid,
-                                         w.head_dim, w.n_outlier) for h in heads]))
-    return tuple(out)
+def qkv_raster(w: Workload, call_index: int = 0, heads=None, workers: int = 1):
+    """Q, K, V as float32 arrays [n_heads_selected, T, H, W, d] holding bf16 values (B = 1).
+    `workers` > 1 draws the independent (tensor, head) streams on a thread pool; the result does
+    not depend on it."""
+    heads = list(range(w.heads) if heads is None else heads)
+    jobs = [(tensor_id, h) for tensor_id in range(3) for h in heads]
+
+    def one(job):
+        return head_tensor(w.config_id, call_index, job[0], job[1], w.grid, w.head_dim, w.n_outlier)
+
+    if workers > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            parts = list(pool.map(one, jobs))
+    else:
+        parts = [one(j) for j in jobs]
+    n = len(heads)
+    return tuple(np.stack(parts[t * n:(t + 1) * n]) for t in range(3))
