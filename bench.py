@@ -38,7 +38,7 @@ def main():
     ap.add_argument("--workload", default="wan14b-720p")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense BF16 / dense FP8 reference runs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the timed CPU oracle sample")
-    ap.add_argument("--cpu-qtiles", type=int, default=48)
+    ap.add_argument("--cpu-qtiles", type=int, default=630)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads shard across GPUs without any "
