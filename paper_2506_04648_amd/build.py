@@ -17,6 +17,9 @@ def build_lib(verbose: bool = False) -> str:
            "-I" + os.path.join(ROOT, "include"),
            # packed fp32 instructions stay off (they are generated from ordinary float code otherwise)
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # MFMA results stay in architectural VGPRs: the softmax VALU code reads them directly
+           # instead of through v_accvgpr moves
+           "-mllvm", "-amdgpu-mfma-vgpr-form",
            "-o", OUT] + [os.path.join(CSRC, s) for s in SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:

@@ -39,6 +39,7 @@ struct AttnArgs {
 };
 
 constexpr float kLog2eOverSqrtD = 0.12751743f;   // log2(e) / sqrt(128)
+constexpr float kLog2Of448 = 8.8073549f;          // log2(448)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -94,12 +95,32 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
 // FP8 E4M3: both products on v_mfma_f32_16x16x128_f8f6f4 (TS = 128) or, for the PV product of
 // 32-token tiles, v_mfma_f32_16x16x32_fp8_fp8.
 // ---------------------------------------------------------------------------------------------
+// Walks the key-tile box of Eq. 2 in (t, h, w) order.
+struct TileWalk {
+    int t0, h0, w0, h1, w1;
+    int vt, vh, vw;
+    int n;                                  // number of tiles in the box
+    __device__ __forceinline__ void init(const AttnArgs& a, int ut, int uh, int uw) {
+        const Geom& G = a.g;
+        t0 = max(0, ut - a.rt); h0 = max(0, uh - a.rh); w0 = max(0, uw - a.rw);
+        const int t1 = min(G.nT - 1, ut + a.rt);
+        h1 = min(G.nH - 1, uh + a.rh); w1 = min(G.nW - 1, uw + a.rw);
+        n = (t1 - t0 + 1) * (h1 - h0 + 1) * (w1 - w0 + 1);
+        vt = t0; vh = h0; vw = w0;
+    }
+    __device__ __forceinline__ void next() {
+        if (++vw > w1) { vw = w0; if (++vh > h1) { vh = h0; ++vt; } }
+    }
+};
+
 template <int TS>
 __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
     constexpr int NB = TS / 16;
     constexpr int NTHR = TS * 2;
-    __shared__ __attribute__((aligned(16))) uint8_t ldsK[TS * 128];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsV[TS * 128];
+    constexpr int CPT = (TS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
+    constexpr int TILE_BYTES = TS * 128;
+    // two buffers of (K tile, V tile): the next tile is written while the current one is read
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2][2][TILE_BYTES];
     int bh, u;
     if (!work_item(a, &bh, &u)) return;
     const Geom& G = a.g;
@@ -115,40 +136,51 @@ __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
         const uint4 lo = p[0], hi = p[1];
         qop[qb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
     }
-    const float sqv = a.sq[tile0 + u];
+    const float sqc = a.sq[tile0 + u] * kLog2eOverSqrtD;
 
     float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};
+    float l_run[2] = {0.f, 0.f};                           // running sum of 448 * P
     v4f acc[2][8];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    const int t0 = max(0, ut - a.rt), t1 = min(G.nT - 1, ut + a.rt);
-    const int h0 = max(0, uh - a.rh), h1 = min(G.nH - 1, uh + a.rh);
-    const int w0 = max(0, uw - a.rw), w1 = min(G.nW - 1, uw + a.rw);
-    const uint4* ldsK4 = reinterpret_cast<const uint4*>(ldsK);
-    const uint4* ldsV4 = reinterpret_cast<const uint4*>(ldsV);
+    TileWalk walk;
+    walk.init(a, ut, uh, uw);
 
-    for (int vt = t0; vt <= t1; ++vt)
-    for (int vh = h0; vh <= h1; ++vh)
-    for (int vw = w0; vw <= w1; ++vw) {
-        const int v = (vt * G.nH + vh) * G.nW + vw;
-        __syncthreads();                                   // everyone is done with the previous tile
-        {
-            const uint4* gk = reinterpret_cast<const uint4*>(a.k + (tile0 + v) * TS * 128);
-            const uint4* gv = reinterpret_cast<const uint4*>(a.v + (tile0 + v) * TS * 128);
-            for (int c = tid; c < TS * 8; c += NTHR) {
-                reinterpret_cast<uint4*>(ldsK)[c] = gk[c];
-                reinterpret_cast<uint4*>(ldsV)[c] = gv[c];
-            }
+    // HBM -> LDS staging is a linear copy done by the load unit itself (global_load_lds_dwordx4:
+    // lane i of a wave deposits its 16 bytes at the wave's LDS base + 16 i), so no VGPRs are spent
+    auto stage = [&](int buf, int v) {
+        const uint4* gk = reinterpret_cast<const uint4*>(a.k + (tile0 + v) * TILE_BYTES);
+        const uint4* gv = reinterpret_cast<const uint4*>(a.v + (tile0 + v) * TILE_BYTES);
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const int chunk0 = c * NTHR + wave * 64;       // wave-uniform
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(gk + chunk0 + lane),
+                (__attribute__((address_space(3))) void*)(&lds[buf][0][chunk0 * 16]), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(gv + chunk0 + lane),
+                (__attribute__((address_space(3))) void*)(&lds[buf][1][chunk0 * 16]), 16, 0, 0);
         }
-        __syncthreads();
-        const float sc = sqv * a.sk[tile0 + v] * kLog2eOverSqrtD;
+    };
+    stage(0, (walk.vt * G.nH + walk.vh) * G.nW + walk.vw);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    for (int it = 0; it < walk.n; ++it) {
+        const int v = (walk.vt * G.nH + walk.vh) * G.nW + walk.vw;
+        const int cls = tile_class(G, walk.vt, walk.vh, walk.vw);
+        const float sc = sqc * a.sk[tile0 + v];
         const float svv = a.sv[tile0 + v];
-        const int cls = tile_class(G, vt, vh, vw);
         if (a.visited && bh == 0 && tid == 0) a.visited[(size_t)u * G.M + v] = 1;
+        walk.next();
+        const bool more = it + 1 < walk.n;
+        // the next tile streams into the other buffer while this one is used
+        if (more) stage((it + 1) & 1, (walk.vt * G.nH + walk.vh) * G.nW + walk.vw);
+        const uint4* ldsK4 = reinterpret_cast<const uint4*>(lds[it & 1][0]);
+        const uint4* ldsV4 = reinterpret_cast<const uint4*>(lds[it & 1][1]);
 
         // S^T = K Q^T for the two query blocks of this wave
         v4f s[2][NB];
@@ -172,35 +204,45 @@ __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
         }
 
         int pb[2][NB];                                     // P^T as packed E4M3, 4 keys per dword
+        float alpha[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            float mx = s[qb][0][0];
+            float mx = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
+                                       __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) mx = __builtin_fmaxf(mx, s[qb][b][r]);
+            for (int b = 1; b < NB; ++b) {
+                mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][0]), s[qb][b][1]);
+                mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][2]), s[qb][b][3]);
+            }
             mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
             mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
             const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(mx * sc));
-            const float alpha = fast_exp2(m_run[qb] - m_new);
+            alpha[qb] = fast_exp2(m_run[qb] - m_new);
             m_run[qb] = m_new;
+            // 448 * 2^(S' - m) = 2^(S' + (log2(448) - m)): the factor 448 rides in the exponent
+            const float cm = kLog2Of448 - m_new;
             float rs = 0.f;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 float p[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, -m_new));
+                    p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm));
                     rs += p[r];
                 }
                 int w = 0;
-                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0] * 448.0f, p[1] * 448.0f, w, false);
-                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[2] * 448.0f, p[3] * 448.0f, w, true);
+                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], w, false);
+                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], w, true);
                 pb[qb][b] = w;
             }
-            l_run[qb] = l_run[qb] * alpha + rs;
+            l_run[qb] = l_run[qb] * alpha[qb] + rs;
+        }
+        // the row reference rarely moves after the first tiles: rescale O only when some row needs it
+        if (__any(alpha[0] != 1.0f || alpha[1] != 1.0f)) {
 #pragma unroll
-            for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= alpha;
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= alpha[qb];
         }
 
         // O^T += s^V_v * (V^T P^T)
@@ -218,7 +260,7 @@ __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
                     acc[qb][cb] += t * svv;
                 }
             } else {
-                const long vop = reinterpret_cast<const long*>(ldsV)[cb * 64 + lane];
+                const long vop = reinterpret_cast<const long*>(ldsV4)[cb * 64 + lane];
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb) {
                     const long pop = (long)(uint32_t)pb[qb][0] | ((long)(uint32_t)pb[qb][1] << 32);
@@ -228,6 +270,9 @@ __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
                 }
             }
         }
+
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the next tile landed
+        __syncthreads();
     }
 
     float inv[2];
@@ -236,7 +281,7 @@ __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
         float l = l_run[qb];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        inv[qb] = l > 0.f ? 1.0f / (448.0f * l) : 0.f;
+        inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
     store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, g, n, acc, inv);
 }

@@ -101,10 +101,12 @@ def fp8_tie_slack(run: GpuRun, head_slot, part):
     sq32 = sq[0, head_slot, part["u"]].cpu().numpy().astype(np.float32)
     sk32 = sk[0, head_slot].cpu().numpy().astype(np.float32)[part["cols"] // g.TS]
     c32 = np.float32(fo.LOG2E / np.sqrt(128.0))
-    sc32 = (sq32 * sk32) * c32                                          # same order as the kernel
+    sc32 = (sq32 * c32) * sk32                                          # same order as the kernel
     m_gpu = np.ceil((raw * sc32[None, :]).max(axis=1)).astype(np.float64)
-    x = (raw.astype(np.float64) * sc32.astype(np.float64)[None, :] - m_gpu[:, None]).astype(np.float32)
-    y_gpu = e4m3.FP8_MAX * np.exp2(x.astype(np.float64))
+    # the kernel carries the factor 448 in the exponent: 2^(fma(raw, sc, log2(448) - m))
+    cm = (np.float32(np.log2(448.0)) - m_gpu.astype(np.float32)).astype(np.float64)
+    x = (raw.astype(np.float64) * sc32.astype(np.float64)[None, :] + cm[:, None]).astype(np.float32)
+    y_gpu = np.exp2(x.astype(np.float64))
     ph_gpu = e4m3.round_to_e4m3(y_gpu) / e4m3.FP8_MAX * np.exp2(m_gpu - part["m"])[:, None]
     d_elem = np.abs(ph_gpu - part["ph"]) + e4m3.rounding_slack(e4m3.FP8_MAX * part["p"], TAU) / e4m3.FP8_MAX
     slack = (d_elem @ np.abs(part["v"])) / part["l"][:, None]
