@@ -41,6 +41,14 @@ struct AttnArgs {
 constexpr float kLog2eOverSqrtD = 0.12751743f;   // log2(e) / sqrt(128)
 constexpr float kLog2Of448 = 8.8073549f;          // log2(448)
 
+// Scales are read-only for the whole launch and indexed uniformly: reading them through the constant
+// address space lets the compiler use scalar loads, which do not queue behind the vector-memory
+// traffic that stages the K/V tiles.
+typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+__device__ __forceinline__ float load_uniform(const float* p, size_t i) {
+    return ((const_f32_ptr)(uintptr_t)p)[i];
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
@@ -113,14 +121,150 @@ struct TileWalk {
     }
 };
 
+// State of one wave of attn_fp8_kernel: two 16-row query blocks, their softmax statistics and
+// output accumulators.
 template <int TS>
-__global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
+struct Fp8Wave {
+    static constexpr int NB = TS / 16;
+    v8i qop[2];
+    float m_run[2];
+    float l_run[2];          // running sum of 448 * P
+    v4f acc[2][8];
+};
+
+__device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
+    return v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+}
+
+// One key tile: S^T = K Q^T, masked online softmax, P quantised to E4M3, O^T += s^V (V^T P^T).
+// ldsK / ldsV are the staged operand tiles (packed layouts of fps_layout.hip).
+template <int TS>
+__device__ __forceinline__ void fp8_tile(Fp8Wave<TS>& w, const AttnArgs& a, const uint8_t* ldsK,
+                                         const uint8_t* ldsV, int lane, int g, float sc, float svv,
+                                         int cls) {
     constexpr int NB = TS / 16;
+    const Geom& G = a.g;
+    const uint4* ldsK4 = reinterpret_cast<const uint4*>(ldsK);
+    const uint4* ldsV4 = reinterpret_cast<const uint4*>(ldsV);
+
+    // K operands are fetched two blocks ahead of the MFMA that consumes them
+    v4f s[2][NB];
+    uint4 klo[2], khi[2];
+    klo[0] = ldsK4[0 * 64 + lane]; khi[0] = ldsK4[1 * 64 + lane];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (b + 1 < NB) {
+            klo[(b + 1) & 1] = ldsK4[((b + 1) * 2 + 0) * 64 + lane];
+            khi[(b + 1) & 1] = ldsK4[((b + 1) * 2 + 1) * 64 + lane];
+        }
+        const v8i kop = make_v8i(klo[b & 1], khi[b & 1]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+            s[qb][b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                kop, w.qop[qb], v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+    }
+    // first V operands are requested now so that they arrive during the softmax
+    uint4 vlo[2], vhi[2];
+    long v32[2];
+    if constexpr (TS == 128) {
+        vlo[0] = ldsV4[0 * 64 + lane]; vhi[0] = ldsV4[1 * 64 + lane];
+    } else {
+        v32[0] = reinterpret_cast<const long*>(ldsV)[0 * 64 + lane];
+    }
+
+    if ((a.partial_cls >> cls) & 1u) {                     // padded keys of a boundary tile: -inf
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const uint32_t bits = G.valid_mask[cls][b >> 1] >> (((b & 1) << 4) + 4 * g);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
+        }
+    }
+
+    int pb[2][NB];                                         // P^T as packed E4M3, 4 keys per dword
+    float alpha[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        float mx = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
+                                   __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
+#pragma unroll
+        for (int b = 1; b < NB; ++b) {
+            mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][0]), s[qb][b][1]);
+            mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][2]), s[qb][b][3]);
+        }
+        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
+        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = __builtin_fmaxf(w.m_run[qb], __builtin_ceilf(mx * sc));
+        alpha[qb] = fast_exp2(w.m_run[qb] - m_new);
+        w.m_run[qb] = m_new;
+        // 448 * 2^(S' - m) = 2^(S' + (log2(448) - m)): the factor 448 rides in the exponent
+        const float cm = kLog2Of448 - m_new;
+        float rs = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float p[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm));
+                rs += p[r];
+            }
+            int pw = 0;
+            pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], pw, false);
+            pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], pw, true);
+            pb[qb][b] = pw;
+        }
+        w.l_run[qb] = w.l_run[qb] * alpha[qb] + rs;
+    }
+    // the row reference rarely moves after the first tiles: rescale O only when some row needs it
+    if (__any(alpha[0] != 1.0f || alpha[1] != 1.0f)) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int cb = 0; cb < 8; ++cb) w.acc[qb][cb] *= alpha[qb];
+    }
+
+    // O^T += s^V_v * (V^T P^T)
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+        if constexpr (TS == 128) {
+            if (cb + 1 < 8) {
+                vlo[(cb + 1) & 1] = ldsV4[((cb + 1) * 2 + 0) * 64 + lane];
+                vhi[(cb + 1) & 1] = ldsV4[((cb + 1) * 2 + 1) * 64 + lane];
+            }
+            const v8i vop = make_v8i(vlo[cb & 1], vhi[cb & 1]);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const v8i pop = v8i{pb[qb][0], pb[qb][1], pb[qb][2], pb[qb][3],
+                                    pb[qb][4], pb[qb][5], pb[qb][6], pb[qb][7]};
+                const v4f t = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                    vop, pop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+                w.acc[qb][cb] += t * svv;
+            }
+        } else {
+            if (cb + 1 < 8) v32[(cb + 1) & 1] = reinterpret_cast<const long*>(ldsV)[(cb + 1) * 64 + lane];
+            const long vop = v32[cb & 1];
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const long pop = (long)(uint32_t)pb[qb][0] | ((long)(uint32_t)pb[qb][1] << 32);
+                const v4f t = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(
+                    vop, pop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                w.acc[qb][cb] += t * svv;
+            }
+        }
+    }
+}
+
+template <int TS>
+__global__ __launch_bounds__(TS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_fp8_kernel(AttnArgs a) {
     constexpr int NTHR = TS * 2;
     constexpr int CPT = (TS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
     constexpr int TILE_BYTES = TS * 128;
-    // two buffers of (K tile, V tile): the next tile is written while the current one is read
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2][2][TILE_BYTES];
+    // Two staging buffers, each (K tile, V tile), as separate objects: the next tile streams into
+    // one while the other is read, and the compiler can tell the two apart.
+    __shared__ __attribute__((aligned(16))) uint8_t ldsA[2][TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t ldsB[2][TILE_BYTES];
     int bh, u;
     if (!work_item(a, &bh, &u)) return;
     const Geom& G = a.g;
@@ -128,30 +272,25 @@ __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
     const size_t tile0 = (size_t)bh * G.M;
 
-    v8i qop[2];
+    Fp8Wave<TS> w;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wave * 32 + qb * 16 + n;
         const uint4* p = reinterpret_cast<const uint4*>(a.q + ((tile0 + u) * TS + row) * 128 + 32 * g);
-        const uint4 lo = p[0], hi = p[1];
-        qop[qb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+        w.qop[qb] = make_v8i(p[0], p[1]);
+        w.m_run[qb] = -INFINITY;
+        w.l_run[qb] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) w.acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
     }
-    const float sqc = a.sq[tile0 + u] * kLog2eOverSqrtD;
-
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};                           // running sum of 448 * P
-    v4f acc[2][8];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb) acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
+    const float sqc = load_uniform(a.sq, tile0 + u) * kLog2eOverSqrtD;
 
     TileWalk walk;
     walk.init(a, ut, uh, uw);
 
     // HBM -> LDS staging is a linear copy done by the load unit itself (global_load_lds_dwordx4:
     // lane i of a wave deposits its 16 bytes at the wave's LDS base + 16 i), so no VGPRs are spent
-    auto stage = [&](int buf, int v) {
+    auto stage = [&](uint8_t (*dst)[TILE_BYTES], int v) {
         const uint4* gk = reinterpret_cast<const uint4*>(a.k + (tile0 + v) * TILE_BYTES);
         const uint4* gv = reinterpret_cast<const uint4*>(a.v + (tile0 + v) * TILE_BYTES);
 #pragma unroll
@@ -159,131 +298,45 @@ __global__ __launch_bounds__(TS * 2) void attn_fp8_kernel(AttnArgs a) {
             const int chunk0 = c * NTHR + wave * 64;       // wave-uniform
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)(gk + chunk0 + lane),
-                (__attribute__((address_space(3))) void*)(&lds[buf][0][chunk0 * 16]), 16, 0, 0);
+                (__attribute__((address_space(3))) void*)(&dst[0][chunk0 * 16]), 16, 0, 0);
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)(gv + chunk0 + lane),
-                (__attribute__((address_space(3))) void*)(&lds[buf][1][chunk0 * 16]), 16, 0, 0);
+                (__attribute__((address_space(3))) void*)(&dst[1][chunk0 * 16]), 16, 0, 0);
         }
     };
-    stage(0, (walk.vt * G.nH + walk.vh) * G.nW + walk.vw);
+    auto tile_id = [&]() { return (walk.vt * G.nH + walk.vh) * G.nW + walk.vw; };
+
+    stage(ldsA, tile_id());
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    for (int it = 0; it < walk.n; ++it) {
-        const int v = (walk.vt * G.nH + walk.vh) * G.nW + walk.vw;
+    // one key tile per half-iteration: compute from `cur` while the next tile lands in `nxt`
+    auto half = [&](uint8_t (*cur)[TILE_BYTES], uint8_t (*nxt)[TILE_BYTES], int it) {
+        const int v = tile_id();
         const int cls = tile_class(G, walk.vt, walk.vh, walk.vw);
-        const float sc = sqc * a.sk[tile0 + v];
-        const float svv = a.sv[tile0 + v];
+        const float sc = sqc * load_uniform(a.sk, tile0 + v);
+        const float svv = load_uniform(a.sv, tile0 + v);
         if (a.visited && bh == 0 && tid == 0) a.visited[(size_t)u * G.M + v] = 1;
         walk.next();
-        const bool more = it + 1 < walk.n;
-        // the next tile streams into the other buffer while this one is used
-        if (more) stage((it + 1) & 1, (walk.vt * G.nH + walk.vh) * G.nW + walk.vw);
-        const uint4* ldsK4 = reinterpret_cast<const uint4*>(lds[it & 1][0]);
-        const uint4* ldsV4 = reinterpret_cast<const uint4*>(lds[it & 1][1]);
-
-        // S^T = K Q^T for the two query blocks of this wave
-        v4f s[2][NB];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const uint4 lo = ldsK4[(b * 2 + 0) * 64 + lane], hi = ldsK4[(b * 2 + 1) * 64 + lane];
-            const v8i kop = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-                s[qb][b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                    kop, qop[qb], v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-        }
-        if ((a.partial_cls >> cls) & 1u) {                 // padded keys of a boundary tile: -inf
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const uint32_t bits = G.valid_mask[cls][b >> 1] >> (((b & 1) << 4) + 4 * g);
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
-            }
-        }
-
-        int pb[2][NB];                                     // P^T as packed E4M3, 4 keys per dword
-        float alpha[2];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            float mx = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
-                                       __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
-#pragma unroll
-            for (int b = 1; b < NB; ++b) {
-                mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][0]), s[qb][b][1]);
-                mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][2]), s[qb][b][3]);
-            }
-            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
-            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(mx * sc));
-            alpha[qb] = fast_exp2(m_run[qb] - m_new);
-            m_run[qb] = m_new;
-            // 448 * 2^(S' - m) = 2^(S' + (log2(448) - m)): the factor 448 rides in the exponent
-            const float cm = kLog2Of448 - m_new;
-            float rs = 0.f;
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float p[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm));
-                    rs += p[r];
-                }
-                int w = 0;
-                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], w, false);
-                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], w, true);
-                pb[qb][b] = w;
-            }
-            l_run[qb] = l_run[qb] * alpha[qb] + rs;
-        }
-        // the row reference rarely moves after the first tiles: rescale O only when some row needs it
-        if (__any(alpha[0] != 1.0f || alpha[1] != 1.0f)) {
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= alpha[qb];
-        }
-
-        // O^T += s^V_v * (V^T P^T)
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
-            if constexpr (TS == 128) {
-                const uint4 lo = ldsV4[(cb * 2 + 0) * 64 + lane], hi = ldsV4[(cb * 2 + 1) * 64 + lane];
-                const v8i vop = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    const v8i pop = v8i{pb[qb][0], pb[qb][1], pb[qb][2], pb[qb][3],
-                                        pb[qb][4], pb[qb][5], pb[qb][6], pb[qb][7]};
-                    const v4f t = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        vop, pop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-                    acc[qb][cb] += t * svv;
-                }
-            } else {
-                const long vop = reinterpret_cast<const long*>(ldsV4)[cb * 64 + lane];
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    const long pop = (long)(uint32_t)pb[qb][0] | ((long)(uint32_t)pb[qb][1] << 32);
-                    const v4f t = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(
-                        vop, pop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-                    acc[qb][cb] += t * svv;
-                }
-            }
-        }
-
+        if (it + 1 < walk.n) stage(nxt, tile_id());
+        fp8_tile<TS>(w, a, cur[0], cur[1], lane, g, sc, svv, cls);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the next tile landed
         __syncthreads();
+    };
+    for (int it = 0; it < walk.n; it += 2) {
+        half(ldsA, ldsB, it);
+        if (it + 1 < walk.n) half(ldsB, ldsA, it + 1);
     }
 
     float inv[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        float l = l_run[qb];
+        float l = w.l_run[qb];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
-    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, g, n, acc, inv);
+    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, g, n, w.acc, inv);
 }
 
 // ---------------------------------------------------------------------------------------------
