@@ -2,8 +2,9 @@
 """Benchmark of the FP8 3D sliding-tile attention hot path on one MI355X.
 
 One "step" is one pass of the whole path over one batch of synthetic Wan2.1-14B 720p-shaped inputs
-already resident in HBM: raster -> tile order (Q,K,V), per-tile FP8 quantisation (Q,K,V), the
-sliding-tile attention kernel, and tile order -> raster of the output.  Prints ONE JSON line.
+already resident in HBM in raster order: tile ordering + per-tile FP8 quantisation of Q, K, V (one
+fused kernel per tensor) and the sliding-tile attention kernel, whose epilogue writes the output
+back in raster order.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-dense] [--no-cpu]
 """
@@ -66,10 +67,8 @@ def main():
 
     # persistent buffers: the timed region allocates nothing
     L = M * TS
-    tiled = [torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev) for _ in range(3)]
     packed = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device=dev) for _ in range(3)]
     scales = [torch.empty((1, w.heads, M), dtype=torch.float32, device=dev) for _ in range(3)]
-    out_tiled = torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev)
     out_raster = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.bfloat16, device=dev)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
@@ -77,25 +76,18 @@ def main():
         if events:
             events[0].record()
         for i in range(3):
-            fps.tile_order(shape, raster[i], out=tiled[i])
+            fps.quantize_tiles(shape, raster[i], i, out=packed[i], scales=scales[i], raster=True)
         if events:
             events[1].record()
-        for i in range(3):
-            fps.quantize_tiles(shape, tiled[i], i, out=packed[i], scales=scales[i])
+        fps.attn_fwd(shape, w.window, fps.PREC_FP8, packed[0], packed[1], packed[2],
+                     scales[0], scales[1], scales[2], out=out_raster, raster_out=True)
         if events:
             events[2].record()
-        fps.attn_fwd(shape, w.window, fps.PREC_FP8, packed[0], packed[1], packed[2],
-                     scales[0], scales[1], scales[2], out=out_tiled)
-        if events:
-            events[3].record()
-        fps.tile_unorder(shape, out_tiled, out=out_raster)
-        if events:
-            events[4].record()
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    all_events = [[ev() for _ in range(5)] for _ in range(args.steps)]
+    all_events = [[ev() for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -103,21 +95,20 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
-    seg = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(4)] for e in all_events])
-    order_ms, quant_ms, attn_ms, unorder_ms = (float(x) for x in seg.mean(axis=0))
+    seg = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(2)] for e in all_events])
+    quant_ms, attn_ms = (float(x) for x in seg.mean(axis=0))
 
     result = {
         "metric": "effective TFLOP/s + ms/call, FP8 3D sliding-tile attention, Wan-14B 720p shape",
         "value": flop / (ms_per_step * 1e-3) / 1e12,
-        "unit": "TFLOP/s (computed tile pairs, whole hot path incl. tile order + quantise)",
+        "unit": "TFLOP/s (computed tile pairs; whole hot path: fused tile-order+quantise x3, attention)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
         "config": {"workload": w.name, "heads": w.heads, "head_dim": w.head_dim, "grid": list(w.grid),
                    "tile": list(w.tile), "window_tiles": list(w.window), "kept_tile_pairs": pairs,
                    "tflop_per_call": flop / 1e12, "input_gen_s": round(gen_s, 1)},
-        "breakdown_ms": {"tile_order_x3": order_ms, "quantize_x3": quant_ms, "attention": attn_ms,
-                         "tile_unorder": unorder_ms},
+        "breakdown_ms": {"tile_order_quantize_x3": quant_ms, "attention_raster_out": attn_ms},
         "attention_tflops": flop / (attn_ms * 1e-3) / 1e12,
         "quantize_GBps": 3.0 * 3 * w.heads * L * 128 / (quant_ms * 1e-3) / 1e9,
         "roofline": {"bound": "mfma", "kernel": "attn_fp8_kernel", "achieved": flop / (attn_ms * 1e-3) / 1e12,
@@ -142,7 +133,10 @@ def main():
             torch.cuda.synchronize()
             return a.elapsed_time(b) / reps
 
+        tiled = [fps.tile_order(shape, r) for r in raster]
+        out_tiled = torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev)
         p16 = [fps.pack_tiles_bf16(shape, tiled[i], i) for i in range(3)]
+        del tiled
         bf16_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_BF16, p16[0][0], p16[1][0], p16[2][0],
                                              sv=p16[2][1], out=out_tiled), 2)
         del p16

@@ -58,6 +58,7 @@ typedef enum {
 
 typedef enum { FPS_ROLE_Q = 0, FPS_ROLE_K = 1, FPS_ROLE_V = 2 } fps_role;
 typedef enum { FPS_OUT_BF16 = 0, FPS_OUT_F32 = 1 } fps_out_dtype;
+typedef enum { FPS_LAYOUT_TILED = 0, FPS_LAYOUT_RASTER = 1 } fps_layout;
 
 typedef struct {
     int B, heads, head_dim;   /* head_dim must be 128                                             */
@@ -123,6 +124,13 @@ int fps_tile_unorder(const fps_shape* shape, const void* o_tiled, fps_out_dtype 
 int fps_quantize_tiles(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
                        fps_vscale vscale, void* xq_out, float* scales_out, void* stream);
 
+/* fps_tile_order fused into fps_quantize_tiles (Sec. 3.2 steps (1)+(2) in one pass over HBM): the
+ * input is the RASTER bf16 tensor [B,heads,T,H,W,128] (device); each workgroup gathers the tokens
+ * of its 3D tile (padded slots read as zero) and proceeds exactly like fps_quantize_tiles.
+ * Outputs, scales and codes are bit-identical to fps_tile_order followed by fps_quantize_tiles. */
+int fps_quantize_raster(const fps_shape* shape, const void* x_raster_bf16, fps_role role,
+                        fps_vscale vscale, void* xq_out, float* scales_out, void* stream);
+
 /* BF16-mode counterpart of fps_quantize_tiles: re-lays a tiled bf16 tensor (device) into the
  * packed operand layout for `role` (device, fps_packed_bytes(shape, FPS_PREC_BF16) bytes).
  * Q and K keep their bf16 values.  V is stored as fp16 after an exact per-tile power-of-two
@@ -150,7 +158,9 @@ int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, in
  *              (may be NULL) and sv is the vscale_out of fps_pack_tiles_bf16.
  *   step       if non-NULL, (prec, win) are replaced by fps_schedule_select(step); the packed
  *              tensors must match the selected precision.
- *   out        tiled [B,heads,M*TS,128] of dtype out_dt (device); padded query rows get 0.
+ *   out        of dtype out_dt (device): tiled [B,heads,M*TS,128] with padded query rows set to 0
+ *              (FPS_LAYOUT_TILED), or raster [B,heads,T,H,W,128] holding the real tokens only
+ *              (FPS_LAYOUT_RASTER: the inverse tile ordering is fused into the epilogue).
  *   visited    NULL, or device memory of M*M bytes zeroed by the caller: the kernel sets
  *              visited[u*M+v] = 1 for every tile pair it computes (written by head 0 only).
  * Scores are dequantised per tile pair (s^Q_u * s^K_v / sqrt(d)); softmax runs online in base 2
@@ -159,7 +169,7 @@ int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, in
 int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision prec,
                  const fps_step_cfg* step, const void* q, const void* k, const void* v,
                  const float* sq, const float* sk, const float* sv, fps_vscale vscale, void* out,
-                 fps_out_dtype out_dt, uint8_t* visited, void* stream);
+                 fps_out_dtype out_dt, fps_layout out_layout, uint8_t* visited, void* stream);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,8 @@ def build_lib(verbose: bool = False) -> str:
            # MFMA results stay in architectural VGPRs: the softmax VALU code reads them directly
            # instead of through v_accvgpr moves
            "-mllvm", "-amdgpu-mfma-vgpr-form",
-           "-o", OUT] + [os.path.join(CSRC, s) for s in SOURCES]
+           "-o", OUT] + os.environ.get("FPS_EXTRA_HIPCC_FLAGS", "").split() \
+          + [os.path.join(CSRC, s) for s in SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(res.stdout)

@@ -13,6 +13,8 @@
 // range of the format).  The denominator accumulates the unrounded P.
 #include "fps_internal.h"
 
+#include <type_traits>
+
 namespace fps {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -33,6 +35,7 @@ struct AttnArgs {
     Geom g;
     int rt, rh, rw;        // window radii in tiles
     int out_f32;
+    int out_raster;        // output in raster order (real tokens only) instead of tile order
     int chunk;             // work items per XCD
     int total;             // BH * M
     uint32_t partial_cls;  // bit c set iff boundary class c has padded tokens
@@ -75,18 +78,27 @@ __device__ __forceinline__ int tile_class(const Geom& g, int t, int h, int w) {
 // Epilogue shared by both precisions: O = acc * inv_l, padded rows zero, fp32 or bf16 store.
 template <int TS>
 __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int ucls, int wave,
-                                           int g, int n, const v4f (&acc)[2][8], const float (&inv)[2]) {
+                                           int g, int n, const v4f (&acc)[2][8], const float (&inv)[2],
+                                           const float* ch_scale = nullptr) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int rr = wave * 32 + qb * 16 + n;
         const bool valid = (a.g.valid_mask[ucls][rr >> 5] >> (rr & 31)) & 1u;
         const float sc = valid ? inv[qb] : 0.0f;
-        const size_t row = ((size_t)bh * a.g.M + u) * TS + rr;
+        size_t row = ((size_t)bh * a.g.M + u) * TS + rr;
+        if (a.out_raster) {                                // token (t,h,w) of in-tile rank rr
+            if (!valid) continue;
+            const Geom& G = a.g;
+            const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
+            const int rw = rr % G.Tw, rh = (rr / G.Tw) % G.Th, rt = rr / (G.Tw * G.Th);
+            row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
+        }
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) {
-            v4f o = acc[qb][cb] * sc;
-            if (!valid) o = v4f{0.f, 0.f, 0.f, 0.f};
             const int col = 16 * cb + 4 * g;
+            v4f o = acc[qb][cb] * sc;
+            if (ch_scale) o *= *reinterpret_cast<const v4f*>(ch_scale + col);
+            if (!valid) o = v4f{0.f, 0.f, 0.f, 0.f};
             if (a.out_f32) {
                 *reinterpret_cast<v4f*>(reinterpret_cast<float*>(a.out) + row * 128 + col) = o;
             } else {
@@ -121,222 +133,302 @@ struct TileWalk {
     }
 };
 
-// State of one wave of attn_fp8_kernel: two 16-row query blocks, their softmax statistics and
-// output accumulators.
-template <int TS>
-struct Fp8Wave {
-    static constexpr int NB = TS / 16;
-    v8i qop[2];
-    float m_run[2];
-    float l_run[2];          // running sum of 448 * P
-    v4f acc[2][8];
-};
-
 __device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
     return v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
 }
 
-// One key tile: S^T = K Q^T, masked online softmax, P quantised to E4M3, O^T += s^V (V^T P^T).
-// ldsK / ldsV are the staged operand tiles (packed layouts of fps_layout.hip).
-template <int TS>
-__device__ __forceinline__ void fp8_tile(Fp8Wave<TS>& w, const AttnArgs& a, const uint8_t* ldsK,
-                                         const uint8_t* ldsV, int lane, int g, float sc, float svv,
-                                         int cls) {
-    constexpr int NB = TS / 16;
-    const Geom& G = a.g;
-    const uint4* ldsK4 = reinterpret_cast<const uint4*>(ldsK);
-    const uint4* ldsV4 = reinterpret_cast<const uint4*>(ldsV);
-
-    // K operands are fetched two blocks ahead of the MFMA that consumes them
-    v4f s[2][NB];
-    uint4 klo[2], khi[2];
-    klo[0] = ldsK4[0 * 64 + lane]; khi[0] = ldsK4[1 * 64 + lane];
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (b + 1 < NB) {
-            klo[(b + 1) & 1] = ldsK4[((b + 1) * 2 + 0) * 64 + lane];
-            khi[(b + 1) & 1] = ldsK4[((b + 1) * 2 + 1) * 64 + lane];
-        }
-        const v8i kop = make_v8i(klo[b & 1], khi[b & 1]);
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-            s[qb][b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                kop, w.qop[qb], v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-    }
-    // first V operands are requested now so that they arrive during the softmax
-    uint4 vlo[2], vhi[2];
-    long v32[2];
-    if constexpr (TS == 128) {
-        vlo[0] = ldsV4[0 * 64 + lane]; vhi[0] = ldsV4[1 * 64 + lane];
-    } else {
-        v32[0] = reinterpret_cast<const long*>(ldsV)[0 * 64 + lane];
-    }
-
-    if ((a.partial_cls >> cls) & 1u) {                     // padded keys of a boundary tile: -inf
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const uint32_t bits = G.valid_mask[cls][b >> 1] >> (((b & 1) << 4) + 4 * g);
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
-        }
-    }
-
-    int pb[2][NB];                                         // P^T as packed E4M3, 4 keys per dword
-    float alpha[2];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        float mx = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
-                                   __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
-#pragma unroll
-        for (int b = 1; b < NB; ++b) {
-            mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][0]), s[qb][b][1]);
-            mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[qb][b][2]), s[qb][b][3]);
-        }
-        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
-        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = __builtin_fmaxf(w.m_run[qb], __builtin_ceilf(mx * sc));
-        alpha[qb] = fast_exp2(w.m_run[qb] - m_new);
-        w.m_run[qb] = m_new;
-        // 448 * 2^(S' - m) = 2^(S' + (log2(448) - m)): the factor 448 rides in the exponent
-        const float cm = kLog2Of448 - m_new;
-        float rs = 0.f;
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            float p[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm));
-                rs += p[r];
-            }
-            int pw = 0;
-            pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], pw, false);
-            pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], pw, true);
-            pb[qb][b] = pw;
-        }
-        w.l_run[qb] = w.l_run[qb] * alpha[qb] + rs;
-    }
-    // the row reference rarely moves after the first tiles: rescale O only when some row needs it
-    if (__any(alpha[0] != 1.0f || alpha[1] != 1.0f)) {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int cb = 0; cb < 8; ++cb) w.acc[qb][cb] *= alpha[qb];
-    }
-
-    // O^T += s^V_v * (V^T P^T)
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-        if constexpr (TS == 128) {
-            if (cb + 1 < 8) {
-                vlo[(cb + 1) & 1] = ldsV4[((cb + 1) * 2 + 0) * 64 + lane];
-                vhi[(cb + 1) & 1] = ldsV4[((cb + 1) * 2 + 1) * 64 + lane];
-            }
-            const v8i vop = make_v8i(vlo[cb & 1], vhi[cb & 1]);
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const v8i pop = v8i{pb[qb][0], pb[qb][1], pb[qb][2], pb[qb][3],
-                                    pb[qb][4], pb[qb][5], pb[qb][6], pb[qb][7]};
-                const v4f t = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                    vop, pop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-                w.acc[qb][cb] += t * svv;
-            }
-        } else {
-            if (cb + 1 < 8) v32[(cb + 1) & 1] = reinterpret_cast<const long*>(ldsV)[(cb + 1) * 64 + lane];
-            const long vop = v32[cb & 1];
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const long pop = (long)(uint32_t)pb[qb][0] | ((long)(uint32_t)pb[qb][1] << 32);
-                const v4f t = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(
-                    vop, pop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-                w.acc[qb][cb] += t * svv;
-            }
-        }
-    }
+// Linear HBM -> LDS copy of one 16-byte chunk per lane, done by the load unit itself: lane i of the
+// wave deposits its chunk at lds_wave_base + 16 i.  Written as inline assembly so that the
+// compiler's wait-count bookkeeping does not serialise it against LDS reads of OTHER buffers; the
+// kernel waits for it explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
+__device__ __forceinline__ void dma_chunk(const void* gsrc_lane, uint32_t lds_wave_base) {
+    lds_wave_base = __builtin_amdgcn_readfirstlane(lds_wave_base);   // wave-uniform by construction
+    asm volatile("s_mov_b32 m0, %1\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gsrc_lane), "s"(lds_wave_base)
+                 : "memory", "m0");
 }
 
-template <int TS>
+// The FP8 kernel is software-pipelined inside each wave, because on this chip a wave whose next
+// instruction is an MFMA holds the vector issue port while the matrix pipe is busy: MFMA and VALU
+// work overlap well only when they alternate within one instruction stream.  Per key tile i:
+//   phase 1: row maxima of S(i) (VALU)            interleaved with  O += s^V (V^T P^T)(i-1) (MFMA)
+//   phase 2: P(i) = 2^(S'(i) - m), FP8 pack (VALU) interleaved with  S(i+1) = K(i+1) Q^T     (MFMA)
+// so the PV product of a tile runs one iteration late and the QK product one iteration early; a
+// score block's registers are recycled for the next tile as soon as its exponentials are taken.
+// K(i+2) and V(i) stream into LDS during iteration i; one barrier per iteration.
+// VCH: V carries one scale per channel (the paper's variant) instead of one per tile; the PV MFMA
+// then accumulates straight into O and the scales are applied once in the epilogue.
+template <int TS, bool VCH>
 __global__ __launch_bounds__(TS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_fp8_kernel(AttnArgs a) {
+    constexpr int NB = TS / 16;
     constexpr int NTHR = TS * 2;
     constexpr int CPT = (TS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
     constexpr int TILE_BYTES = TS * 128;
-    // Two staging buffers, each (K tile, V tile), as separate objects: the next tile streams into
-    // one while the other is read, and the compiler can tell the two apart.
-    __shared__ __attribute__((aligned(16))) uint8_t ldsA[2][TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsB[2][TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[4][TILE_BYTES];   // K even, K odd, V even, V odd
     int bh, u;
     if (!work_item(a, &bh, &u)) return;
     const Geom& G = a.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
     const size_t tile0 = (size_t)bh * G.M;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(&lds[0][0]);   // LDS byte address of buffer 0
 
-    Fp8Wave<TS> w;
+    v8i qop[2];
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.f, 0.f};                           // running sum of 448 * P
+    float alpha_prev[2] = {1.f, 1.f};                      // rescale owed to O before the delayed PV
+    v4f acc[2][8];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wave * 32 + qb * 16 + n;
         const uint4* p = reinterpret_cast<const uint4*>(a.q + ((tile0 + u) * TS + row) * 128 + 32 * g);
-        w.qop[qb] = make_v8i(p[0], p[1]);
-        w.m_run[qb] = -INFINITY;
-        w.l_run[qb] = 0.f;
+        qop[qb] = make_v8i(p[0], p[1]);
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) w.acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int cb = 0; cb < 8; ++cb) acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
     }
     const float sqc = load_uniform(a.sq, tile0 + u) * kLog2eOverSqrtD;
 
-    TileWalk walk;
-    walk.init(a, ut, uh, uw);
+    TileWalk w0, w2;                                       // tile i, and the tile whose K is fetched (i+2)
+    w0.init(a, ut, uh, uw);
+    w2 = w0;
+    const int ntiles = w0.n;
+    auto tile_of = [&](const TileWalk& w) { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
 
-    // HBM -> LDS staging is a linear copy done by the load unit itself (global_load_lds_dwordx4:
-    // lane i of a wave deposits its 16 bytes at the wave's LDS base + 16 i), so no VGPRs are spent
-    auto stage = [&](uint8_t (*dst)[TILE_BYTES], int v) {
-        const uint4* gk = reinterpret_cast<const uint4*>(a.k + (tile0 + v) * TILE_BYTES);
-        const uint4* gv = reinterpret_cast<const uint4*>(a.v + (tile0 + v) * TILE_BYTES);
+    // chunk c (of CPT) of this thread's share of one operand tile, HBM -> lds[buf]
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) {
+        const int chunk0 = c * NTHR + wave * 64;           // wave-uniform
+        dma_chunk(reinterpret_cast<const uint4*>(src) + chunk0 + lane,
+                  lds_base + buf * TILE_BYTES + chunk0 * 16);
+    };
+    auto stage = [&](int buf, const uint8_t* src) {
 #pragma unroll
-        for (int c = 0; c < CPT; ++c) {
-            const int chunk0 = c * NTHR + wave * 64;       // wave-uniform
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gk + chunk0 + lane),
-                (__attribute__((address_space(3))) void*)(&dst[0][chunk0 * 16]), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gv + chunk0 + lane),
-                (__attribute__((address_space(3))) void*)(&dst[1][chunk0 * 16]), 16, 0, 0);
+        for (int c = 0; c < CPT; ++c) stage_chunk(buf, src, c);
+    };
+    auto k_tile = [&](int v) { return a.k + (tile0 + v) * TILE_BYTES; };
+    auto v_tile = [&](int v) { return a.v + (tile0 + v) * TILE_BYTES; };
+
+    v4f s[2][NB];
+    v8i pb[2];                                             // P^T as packed E4M3, 4 keys per dword
+    pb[0] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+    pb[1] = pb[0];
+
+    auto load_k = [&](const uint8_t* ldsK, int b) {
+        const uint4* k4 = reinterpret_cast<const uint4*>(ldsK);
+        return make_v8i(k4[(b * 2 + 0) * 64 + lane], k4[(b * 2 + 1) * 64 + lane]);
+    };
+    auto qk_mfma = [&](const v8i& kop, int b) {            // S(b) = K(b) Q^T for both query blocks
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+            s[qb][b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                kop, qop[qb], v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+    };
+    auto load_v = [&](const uint8_t* ldsV, int cb) {
+        if constexpr (TS == 128) {
+            const uint4* v4 = reinterpret_cast<const uint4*>(ldsV);
+            return make_v8i(v4[(cb * 2 + 0) * 64 + lane], v4[(cb * 2 + 1) * 64 + lane]);
+        } else {
+            const uint2 x = reinterpret_cast<const uint2*>(ldsV)[cb * 64 + lane];
+            return v8i{(int)x.x, (int)x.y, 0, 0, 0, 0, 0, 0};
         }
     };
-    auto tile_id = [&]() { return (walk.vt * G.nH + walk.vh) * G.nW + walk.vw; };
+    // V^T(cb) P^T for both query blocks: raw into t (per-tile V scales) or accumulated into O (VCH)
+    auto pv_mfma = [&](const v8i& vop, v4f (&t)[2], int cb) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const v4f c_in = VCH ? acc[qb][cb] : v4f{0.f, 0.f, 0.f, 0.f};
+            v4f r;
+            if constexpr (TS == 128) {
+                r = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(vop, pb[qb], c_in, 0, 0, 0, 0, 0, 0);
+            } else {
+                const long va = (long)(uint32_t)vop[0] | ((long)(uint32_t)vop[1] << 32);
+                const long pa = (long)(uint32_t)pb[qb][0] | ((long)(uint32_t)pb[qb][1] << 32);
+                r = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(va, pa, c_in, 0, 0, 0);
+            }
+            if (VCH) acc[qb][cb] = r; else t[qb] = r;
+        }
+    };
+    // O^T(cb) += s^V * t, pinned where it is written so that t does not stay live (the compiler
+    // otherwise sinks all sixteen updates below the loop and spills)
+    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) {
+        if (VCH) return;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            acc[qb][cb] += t[qb] * svv;
+            asm volatile("" : "+v"(acc[qb][cb]));
+        }
+    };
+    auto mask_scores = [&](int cls) {                      // padded keys of a boundary tile: -inf
+        if ((a.partial_cls >> cls) & 1u) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const uint32_t bits = G.valid_mask[cls][b >> 1] >> (((b & 1) << 4) + 4 * g);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
+            }
+        }
+    };
+    auto rescale_acc = [&]() {                             // the row reference rarely moves
+        if (__any(alpha_prev[0] != 1.0f || alpha_prev[1] != 1.0f)) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= alpha_prev[qb];
+        }
+    };
 
-    stage(ldsA, tile_id());
+    // prologue: K(0), K(1) staged; S(0) computed
+    stage(0, k_tile(tile_of(w2)));
+    w2.next();
+    if (ntiles > 1) { stage(1, k_tile(tile_of(w2))); w2.next(); }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+#pragma unroll
+    for (int b = 0; b < NB; ++b) qk_mfma(load_k(lds[0], b), b);
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
 
-    // one key tile per half-iteration: compute from `cur` while the next tile lands in `nxt`
-    auto half = [&](uint8_t (*cur)[TILE_BYTES], uint8_t (*nxt)[TILE_BYTES], int it) {
-        const int v = tile_id();
-        const int cls = tile_class(G, walk.vt, walk.vh, walk.vw);
-        const float sc = sqc * load_uniform(a.sk, tile0 + v);
-        const float svv = load_uniform(a.sv, tile0 + v);
+    float svv_prev = 0.f;
+    float sc_next = sqc * load_uniform(a.sk, tile0 + tile_of(w0));   // scales of the coming tile
+    float sv_next = VCH ? 1.f : load_uniform(a.sv, tile0 + tile_of(w0));
+    // One iteration.  FIRST: there is no previous tile whose PV is owed.  LAST: there is no next
+    // tile whose scores can be started.  Both are compile-time so that the MFMA / VALU interleave
+    // of the steady state carries no branches.
+    auto iteration = [&](auto first_tag, auto last_tag, int it) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        constexpr bool LAST = decltype(last_tag)::value;
+        const int par = it & 1;
+        const uint8_t* knxt = lds[par ^ 1];                // K(i+1)
+        const uint8_t* vprev = lds[2 + (par ^ 1)];         // V(i-1)
+        const int v = tile_of(w0);
+        const float sc = sc_next;
+        const float svv = sv_next;
         if (a.visited && bh == 0 && tid == 0) a.visited[(size_t)u * G.M + v] = 1;
-        walk.next();
-        if (it + 1 < walk.n) stage(nxt, tile_id());
-        fp8_tile<TS>(w, a, cur[0], cur[1], lane, g, sc, svv, cls);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the next tile landed
-        __syncthreads();
+        __syncthreads();                 // every wave is past QK(i) and PV(i-2); staged tiles are visible
+        // K(i+2) replaces K(i), V(i) goes to its own buffer; the copies are issued between the
+        // MFMAs of phase 1 rather than in one burst (the load unit takes them slowly)
+        const bool fetch_k = it + 2 < ntiles;
+        const uint8_t* ksrc = fetch_k ? k_tile(tile_of(w2)) : nullptr;
+        const uint8_t* vsrc = v_tile(v);
+        if (fetch_k) w2.next();
+        w0.next();
+        if (!LAST) {                     // scales of tile i+1, needed next iteration
+            const int vn = tile_of(w0);
+            sc_next = sqc * load_uniform(a.sk, tile0 + vn);
+            if (!VCH) sv_next = load_uniform(a.sv, tile0 + vn);
+        }
+
+        // ---- phase 1: row maxima of S(i)  |  delayed PV(i-1) --------------------------------
+        if (!FIRST) rescale_acc();
+        float mx[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+            mx[qb] = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
+                                     __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
+        v4f tq[2][2];                                      // MFMA results wait one block for their fma
+        v8i vop[2];
+        if (!FIRST) vop[0] = load_v(vprev, 0);
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+            if (!FIRST) {
+                if (cb + 1 < 8) vop[(cb + 1) & 1] = load_v(vprev, cb + 1);
+                pv_mfma(vop[cb & 1], tq[cb & 1], cb);
+                if (cb > 0) pv_accumulate(cb - 1, tq[(cb - 1) & 1], svv_prev);
+            }
+            if (cb >= 1 && cb < NB) {
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    mx[qb] = __builtin_fmaxf(__builtin_fmaxf(mx[qb], s[qb][cb][0]), s[qb][cb][1]);
+                    mx[qb] = __builtin_fmaxf(__builtin_fmaxf(mx[qb], s[qb][cb][2]), s[qb][cb][3]);
+                }
+            }
+            if (cb < CPT) stage_chunk(2 + par, vsrc, cb);
+            else if (cb < 2 * CPT && fetch_k) stage_chunk(par, ksrc, cb - CPT);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        static_assert(2 * CPT <= 8, "staging is spread over the 8 channel blocks of phase 1");
+        if (!FIRST) pv_accumulate(7, tq[1], svv_prev);
+        float cm[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float t = mx[qb];
+            t = __builtin_fmaxf(t, __shfl_xor(t, 16));
+            t = __builtin_fmaxf(t, __shfl_xor(t, 32));
+            const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(t * sc));
+            alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
+            m_run[qb] = m_new;
+            // 448 * 2^(S' - m) = 2^(S' + (log2(448) - m)): the factor 448 rides in the exponent
+            cm[qb] = kLog2Of448 - m_new;
+        }
+
+        // ---- phase 2: P(i) and its FP8 codes  |  early QK(i+1) ------------------------------
+        float rs[2] = {0.f, 0.f};
+        v8i kop[2];
+        if (!LAST) kop[0] = load_k(knxt, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (!LAST && b + 1 < NB) kop[(b + 1) & 1] = load_k(knxt, b + 1);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                float p[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm[qb]));
+                    rs[qb] += p[r];
+                }
+                int pw = 0;
+                pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], pw, false);
+                pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], pw, true);
+                // pinned here: otherwise the compiler sinks the whole exponential pass below the
+                // MFMAs it is meant to overlap with
+                asm volatile("" : "+v"(pw), "+v"(rs[qb]));
+                pb[qb][b] = pw;
+            }
+            if (!LAST) qk_mfma(kop[b & 1], b);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
+        svv_prev = svv;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the staged tiles landed
     };
-    for (int it = 0; it < walk.n; it += 2) {
-        half(ldsA, ldsB, it);
-        if (it + 1 < walk.n) half(ldsB, ldsA, it + 1);
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    if (ntiles == 1) {
+        iteration(T_{}, T_{}, 0);
+    } else {
+        iteration(T_{}, F_{}, 0);
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{}, it);
+        iteration(F_{}, T_{}, ntiles - 1);
+    }
+    // epilogue: the last tile's PV
+    __syncthreads();
+    rescale_acc();
+    {
+        const uint8_t* vlast = lds[2 + ((ntiles - 1) & 1)];
+        v4f tq[2];
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+            pv_mfma(load_v(vlast, cb), tq, cb);
+            pv_accumulate(cb, tq, svv_prev);
+        }
     }
 
     float inv[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        float l = w.l_run[qb];
+        float l = l_run[qb];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
-    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, g, n, w.acc, inv);
+    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, g, n, acc, inv,
+                   VCH ? a.sv + (size_t)bh * 128 : nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -522,11 +614,7 @@ int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u
 
 int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, const void* k,
                 const void* v, const float* sq, const float* sk, const float* sv, int vscale,
-                void* out, int out_f32, uint8_t* visited, hipStream_t st) {
-    if (prec == FPS_PREC_FP8 && vscale != FPS_VSCALE_TILE) {
-        set_error("per-channel V scales are not implemented yet");
-        return FPS_ERR_UNSUPPORTED;
-    }
+                void* out, int out_f32, int out_raster, uint8_t* visited, hipStream_t st) {
     AttnArgs a;
     a.q = (const uint8_t*)q; a.k = (const uint8_t*)k; a.v = (const uint8_t*)v;
     a.sq = sq; a.sk = sk; a.sv = sv;
@@ -534,6 +622,7 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     a.g = g;
     a.rt = win.wt / 2; a.rh = win.wh / 2; a.rw = win.ww / 2;
     a.out_f32 = out_f32;
+    a.out_raster = out_raster;
     a.total = g.BH * g.M;
     a.chunk = (a.total + 7) / 8;
     a.partial_cls = 0;
@@ -543,8 +632,14 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
             if (g.valid_mask[c][w] != 0xFFFFFFFFu) a.partial_cls |= 1u << c;
     const int grid = a.chunk * 8;
     if (prec == FPS_PREC_FP8) {
-        if (g.TS == 128) attn_fp8_kernel<128><<<grid, 256, 0, st>>>(a);
-        else             attn_fp8_kernel<32><<<grid, 64, 0, st>>>(a);
+        const bool vch = vscale == FPS_VSCALE_CHANNEL;
+        if (g.TS == 128) {
+            if (vch) attn_fp8_kernel<128, true><<<grid, 256, 0, st>>>(a);
+            else     attn_fp8_kernel<128, false><<<grid, 256, 0, st>>>(a);
+        } else {
+            if (vch) attn_fp8_kernel<32, true><<<grid, 64, 0, st>>>(a);
+            else     attn_fp8_kernel<32, false><<<grid, 64, 0, st>>>(a);
+        }
     } else {
         if (g.TS == 128) attn_bf16_kernel<128><<<grid, 256, 0, st>>>(a);
         else             attn_bf16_kernel<32><<<grid, 64, 0, st>>>(a);

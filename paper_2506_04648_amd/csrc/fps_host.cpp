@@ -188,7 +188,20 @@ int fps_quantize_tiles(const fps_shape* shape, const void* x_tiled_bf16, fps_rol
     FPS_TRY(check_ptr(xq_out, "xq_out"));
     FPS_TRY(check_ptr(scales_out, "scales_out"));
     const int vs = role == FPS_ROLE_V ? (int)vscale : (int)FPS_VSCALE_TILE;
-    return launch_quantize(g, x_tiled_bf16, role, vs, xq_out, scales_out, (hipStream_t)stream);
+    return launch_quantize(g, x_tiled_bf16, 0, role, vs, xq_out, scales_out, (hipStream_t)stream);
+}
+
+int fps_quantize_raster(const fps_shape* shape, const void* x_raster_bf16, fps_role role,
+                        fps_vscale vscale, void* xq_out, float* scales_out, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_enum(role, FPS_ROLE_V, "role"));
+    FPS_TRY(check_enum(vscale, FPS_VSCALE_CHANNEL, "vscale"));
+    FPS_TRY(check_ptr(x_raster_bf16, "x_raster_bf16"));
+    FPS_TRY(check_ptr(xq_out, "xq_out"));
+    FPS_TRY(check_ptr(scales_out, "scales_out"));
+    const int vs = role == FPS_ROLE_V ? (int)vscale : (int)FPS_VSCALE_TILE;
+    return launch_quantize(g, x_raster_bf16, 1, role, vs, xq_out, scales_out, (hipStream_t)stream);
 }
 
 int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
@@ -229,7 +242,7 @@ int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, in
 int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision prec,
                  const fps_step_cfg* step, const void* q, const void* k, const void* v,
                  const float* sq, const float* sk, const float* sv, fps_vscale vscale, void* out,
-                 fps_out_dtype out_dt, uint8_t* visited, void* stream) {
+                 fps_out_dtype out_dt, fps_layout out_layout, uint8_t* visited, void* stream) {
     Geom g;
     FPS_TRY(check_shape(shape, &g));
     fps_regime sel;
@@ -243,6 +256,7 @@ int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision pr
     }
     FPS_TRY(check_enum(vscale, FPS_VSCALE_CHANNEL, "vscale"));
     FPS_TRY(check_enum(out_dt, FPS_OUT_F32, "out_dt"));
+    FPS_TRY(check_enum(out_layout, FPS_LAYOUT_RASTER, "out_layout"));
     FPS_TRY(check_ptr(q, "q"));
     FPS_TRY(check_ptr(k, "k"));
     FPS_TRY(check_ptr(v, "v"));
@@ -253,7 +267,8 @@ int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision pr
     }
     FPS_TRY(check_ptr(sv, "sv"));
     return launch_attn(g, sel.win, sel.prec, q, k, v, sq, sk, sv, vscale, out,
-                       out_dt == FPS_OUT_F32, visited, (hipStream_t)stream);
+                       out_dt == FPS_OUT_F32, out_layout == FPS_LAYOUT_RASTER, visited,
+                       (hipStream_t)stream);
 }
 
 }  // extern "C"

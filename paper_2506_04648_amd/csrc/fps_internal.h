@@ -30,13 +30,13 @@ int hip_fail(hipError_t e, const char* what);          // records and returns FP
 // kernel launchers (defined in the .hip files); all arguments already validated
 int launch_tile_order(const Geom& g, const void* in, void* out, hipStream_t st);
 int launch_tile_unorder(const Geom& g, const void* in, int elem_bytes, void* out, hipStream_t st);
-int launch_quantize(const Geom& g, const void* x, int role, int vscale, void* xq, float* scales,
-                    hipStream_t st);
+int launch_quantize(const Geom& g, const void* x, int raster, int role, int vscale, void* xq,
+                    float* scales, hipStream_t st);
 int launch_pack_bf16(const Geom& g, const void* x, int role, void* xp, float* vscale, hipStream_t st);
 int launch_unpack_q8(const Geom& g, const void* xq, int role, uint8_t* out, hipStream_t st);
 int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, const void* k,
                 const void* v, const float* sq, const float* sk, const float* sv, int vscale,
-                void* out, int out_f32, uint8_t* visited, hipStream_t st);
+                void* out, int out_f32, int out_raster, uint8_t* visited, hipStream_t st);
 
 int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int v, float* out,
                       hipStream_t st);

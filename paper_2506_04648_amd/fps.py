@@ -21,9 +21,11 @@ PREC_BF16, PREC_FP8 = 0, 1
 VSCALE_TILE, VSCALE_CHANNEL = 0, 1
 ROLE_Q, ROLE_K, ROLE_V = 0, 1, 2
 OUT_BF16, OUT_F32 = 0, 1
+LAYOUT_TILED, LAYOUT_RASTER = 0, 1
 
 EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_packed_bytes",
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
+           "fps_quantize_raster",
            "fps_pack_tiles_bf16", "fps_debug_unpack_q8", "fps_debug_scores_q8", "fps_attn_fwd")
 
 
@@ -74,11 +76,12 @@ def lib():
         L.fps_tile_order.argtypes = [ctypes.POINTER(Shape), vp, vp, vp]
         L.fps_tile_unorder.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp]
         L.fps_quantize_tiles.argtypes = [ctypes.POINTER(Shape), vp, ip, ip, vp, vp, vp]
+        L.fps_quantize_raster.argtypes = [ctypes.POINTER(Shape), vp, ip, ip, vp, vp, vp]
         L.fps_pack_tiles_bf16.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp, vp]
         L.fps_debug_unpack_q8.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp]
         L.fps_debug_scores_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, vp, vp]
         L.fps_attn_fwd.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), ip,
-                                   ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, vp, vp]
+                                   ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, ip, vp, vp]
         for name in EXPORTS:
             if name not in ("fps_last_error", "fps_num_tiles", "fps_packed_bytes"):
                 getattr(L, name).restype = ctypes.c_int
@@ -175,7 +178,10 @@ def tile_unorder(shape: Shape, o_tiled, out=None):
     return out
 
 
-def quantize_tiles(shape: Shape, x_tiled, role, vscale=VSCALE_TILE, out=None, scales=None):
+def quantize_tiles(shape: Shape, x_tiled, role, vscale=VSCALE_TILE, out=None, scales=None,
+                   raster=False):
+    """Per-tile FP8 quantisation of a tile-ordered tensor, or (raster=True) of a raster tensor with
+    the tile ordering fused in.  Returns (packed codes, scales)."""
     import torch
     assert x_tiled.dtype == torch.bfloat16 and x_tiled.is_cuda and x_tiled.is_contiguous()
     if out is None:
@@ -183,8 +189,8 @@ def quantize_tiles(shape: Shape, x_tiled, role, vscale=VSCALE_TILE, out=None, sc
     if scales is None:
         n = shape.head_dim if (role == ROLE_V and vscale == VSCALE_CHANNEL) else num_tiles(shape)
         scales = torch.empty((shape.B, shape.heads, n), dtype=torch.float32, device=x_tiled.device)
-    _check(lib().fps_quantize_tiles(ctypes.byref(shape), _ptr(x_tiled), role, vscale, _ptr(out),
-                                    _ptr(scales), _stream()))
+    fn = lib().fps_quantize_raster if raster else lib().fps_quantize_tiles
+    _check(fn(ctypes.byref(shape), _ptr(x_tiled), role, vscale, _ptr(out), _ptr(scales), _stream()))
     return out, scales
 
 
@@ -220,16 +226,18 @@ def debug_scores_q8(shape: Shape, q8, k8, bh, u, v):
 
 
 def attn_fwd(shape: Shape, window, prec, q, k, v, sq=None, sk=None, sv=None, vscale=VSCALE_TILE,
-             out=None, out_dtype=None, visited=None, step: StepCfg = None):
+             out=None, out_dtype=None, visited=None, step: StepCfg = None, raster_out=False):
     import torch
     if out is None:
         out_dtype = out_dtype or torch.bfloat16
-        out = torch.empty((shape.B, shape.heads, _tiled_len(shape), shape.head_dim), dtype=out_dtype,
-                          device=q.device)
+        dims = ((shape.T, shape.H, shape.W, shape.head_dim) if raster_out
+                else (_tiled_len(shape), shape.head_dim))
+        out = torch.empty((shape.B, shape.heads) + dims, dtype=out_dtype, device=q.device)
     dt = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
     win = Window(*window) if window is not None else None
     _check(lib().fps_attn_fwd(ctypes.byref(shape), ctypes.byref(win) if win is not None else None,
                               prec, ctypes.byref(step) if step is not None else None,
                               _ptr(q), _ptr(k), _ptr(v), _ptr(sq), _ptr(sk), _ptr(sv), vscale,
-                              _ptr(out), dt, _ptr(visited), _stream()))
+                              _ptr(out), dt, LAYOUT_RASTER if raster_out else LAYOUT_TILED,
+                              _ptr(visited), _stream()))
     return out

@@ -40,24 +40,27 @@ class GpuRun:
         self.shape = fps.make_shape(len(self.heads), w.grid, w.tile)
         self.g = geometry(w)
         self.qkv = synth.qkv_raster(w, call_index, self.heads) if qkv is None else qkv
-        self.tiled = [fps.tile_order(self.shape, to_device_bf16(a[None])) for a in self.qkv]
+        self.raster = [to_device_bf16(a[None]) for a in self.qkv]
+        self.tiled = [fps.tile_order(self.shape, r) for r in self.raster]
         self.torch = torch
 
-    def quantize(self):
-        self.q8 = [fps.quantize_tiles(self.shape, t, r) for t, r in zip(self.tiled, (0, 1, 2))]
+    def quantize(self, vscale=fps.VSCALE_TILE):
+        self.q8 = [fps.quantize_tiles(self.shape, t, r, vscale=vscale) for t, r in zip(self.tiled, (0, 1, 2))]
+        self.q8_vscale = vscale
         return self.q8
 
     def pack_bf16(self):
         self.p16 = [fps.pack_tiles_bf16(self.shape, t, r) for t, r in zip(self.tiled, (0, 1, 2))]
         return self.p16
 
-    def attn(self, prec, window=None, out_dtype=None, visited=False, step=None):
+    def attn(self, prec, window=None, out_dtype=None, visited=False, step=None, raster_out=False,
+             vscale=fps.VSCALE_TILE):
         torch = self.torch
         out_dtype = out_dtype or torch.float32
         vis = torch.zeros((self.g.M, self.g.M), dtype=torch.uint8, device="cuda:0") if visited else None
         if prec == fps.PREC_FP8:
-            if not hasattr(self, "q8"):
-                self.quantize()
+            if not hasattr(self, "q8") or self.q8_vscale != vscale:
+                self.quantize(vscale)
             (q, sq), (k, sk), (v, sv) = self.q8
         else:
             if not hasattr(self, "p16"):
@@ -65,8 +68,8 @@ class GpuRun:
             (q, _), (k, _), (v, sv) = self.p16
             sq = sk = None
         window = self.w.window if window is None else window
-        out = fps.attn_fwd(self.shape, window, prec, q, k, v, sq, sk, sv, out_dtype=out_dtype,
-                           visited=vis, step=step)
+        out = fps.attn_fwd(self.shape, window, prec, q, k, v, sq, sk, sv, vscale=vscale,
+                           out_dtype=out_dtype, visited=vis, step=step, raster_out=raster_out)
         torch.cuda.synchronize()
         return (out, vis) if visited else out
 
@@ -115,13 +118,14 @@ def fp8_tie_slack(run: GpuRun, head_slot, part):
     return slack, flips, ph_gpu.size
 
 
-def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None):
+def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None, vscale=fps.VSCALE_TILE):
     """Oracle vs GPU for one head (optionally a subset of query tiles).  Returns a dict of
     normalised errors; asserts nothing."""
     g = run.g
     qt, kt, vt = run.oracle_inputs(head_slot)
     oprec = fo.PREC_FP8 if prec == fps.PREC_FP8 else fo.PREC_BF16
-    ref, parts = fo.attention(qt, kt, vt, g, window, prec=oprec, q_tiles=q_tiles, return_parts=True)
+    ref, parts = fo.attention(qt, kt, vt, g, window, prec=oprec, q_tiles=q_tiles, return_parts=True,
+                              vscale=fo.VSCALE_CHANNEL if vscale == fps.VSCALE_CHANNEL else fo.VSCALE_TILE)
     slack = np.zeros_like(ref)
     flips = elems = 0
     if prec == fps.PREC_FP8:

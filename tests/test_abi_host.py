@@ -97,12 +97,15 @@ def test_device_entry_points_validate_before_launching():
     assert L.fps_debug_unpack_q8(S, good, 0, odd, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_tile_unorder(S, good, 7, good, None) == fps.FPS_ERR_INVALID_ARG
     bad_win = fps.Window(0, 3, 3)
-    args = (good, good, good, good, good, good, 0, good, 1, None, None)
+    args = (good, good, good, good, good, good, 0, good, 1, 0, None, None)
     assert L.fps_attn_fwd(S, ctypes.byref(bad_win), 1, None, *args) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_attn_fwd(S, ctypes.byref(win), 2, None, *args) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_attn_fwd(S, None, 1, None, *args) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_attn_fwd(S, ctypes.byref(win), 1, None, good, good, good, None, good, good, 0,
-                          good, 1, None, None) == fps.FPS_ERR_INVALID_ARG      # FP8 needs scales
+                          good, 1, 0, None, None) == fps.FPS_ERR_INVALID_ARG   # FP8 needs scales
+    assert L.fps_attn_fwd(S, ctypes.byref(win), 1, None, good, good, good, good, good, good, 0,
+                          good, 1, 2, None, None) == fps.FPS_ERR_INVALID_ARG   # bad output layout
+    assert L.fps_quantize_raster(S, good, 0, 0, None, good, None) == fps.FPS_ERR_INVALID_ARG
     big = fps.make_shape(2, (4, 16, 16), (2, 8, 4))                             # 64-token tiles
     assert L.fps_attn_fwd(ctypes.byref(big), ctypes.byref(win), 1, None, *args) == fps.FPS_ERR_UNSUPPORTED
     cfg = fps.make_step_cfg(99, 50, 0.2, 0.5, [(1, (3, 3, 3))] * 3)

@@ -183,6 +183,32 @@ def test_attention_small_shapes(prec, grid, tile, window):
         gu.assert_parity(st, f"{grid} {tile} {window} head {h}")
 
 
+@pytest.mark.parametrize("grid,tile,window", [((4, 16, 16), (2, 4, 4), (1, 3, 3)),
+                                              ((2, 13, 40), (1, 8, 16), (3, 3, 3))])
+def test_per_channel_v_scales(grid, tile, window):
+    """The paper's own V quantisation (Sec. 3.2): one scale per channel over all tokens."""
+    import torch
+    say("per-channel V", grid, tile)
+    w = dataclasses.replace(synth.TINY, grid=grid, tile=tile, window=window, heads=2, n_outlier=3,
+                            config_id=13)
+    run = gu.GpuRun(w)
+    xq, sc = fps.quantize_tiles(run.shape, run.tiled[2], fps.ROLE_V, vscale=fps.VSCALE_CHANNEL)
+    xq_r, sc_r = fps.quantize_tiles(run.shape, run.raster[2], fps.ROLE_V, vscale=fps.VSCALE_CHANNEL,
+                                    raster=True)
+    assert torch.equal(xq, xq_r) and torch.equal(sc, sc_r) and sc.shape == (1, 2, 128)
+    codes = fps.debug_unpack_q8(run.shape, xq, fps.ROLE_V)[0].cpu().numpy()
+    for h in range(2):
+        wc, ws = fo.quantize_channels(fo.tile_order(run.qkv[2][h].astype(np.float64), run.g))
+        assert np.array_equal(sc[0, h].cpu().numpy(), ws)
+        zero_sign = ((codes[h] ^ wc) == 0x80) & ((wc & 0x7F) == 0)
+        assert int(((codes[h] != wc) & ~zero_sign).sum()) == 0
+    out = run.attn(fps.PREC_FP8, vscale=fps.VSCALE_CHANNEL)
+    for h in range(2):
+        st = gu.compare_head(run, out, h, fps.PREC_FP8, window, vscale=fps.VSCALE_CHANNEL)
+        say("  head", h, st)
+        gu.assert_parity(st, f"per-channel V head {h}")
+
+
 def test_shared_outlier_channels_stress():
     """Q and K share their outlier channels: the score spread is ~10x larger (|S'| ~ 100, rows
     close to one-hot), outside the input distribution the tolerances are stated for.  The error of
@@ -228,6 +254,28 @@ def test_bf16_output_is_rounded_fp32_output(tiny):
     o32 = tiny.attn(fps.PREC_FP8, out_dtype=torch.float32)
     o16 = tiny.attn(fps.PREC_FP8, out_dtype=torch.bfloat16)
     assert torch.equal(o16, o32.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("grid,tile", [((4, 16, 16), (2, 4, 4)), ((3, 5, 6), (2, 4, 4)),
+                                       ((2, 13, 40), (1, 8, 16))])
+def test_fused_raster_entry_points_match_the_unfused_path(grid, tile):
+    """fps_quantize_raster == fps_tile_order + fps_quantize_tiles (bit for bit), and the raster
+    output layout of fps_attn_fwd == fps_tile_unorder of the tiled output."""
+    import torch
+    say("fused raster", grid, tile)
+    w = dataclasses.replace(synth.TINY, grid=grid, tile=tile, window=(3, 3, 3), heads=2, n_outlier=3,
+                            config_id=12)
+    run = gu.GpuRun(w)
+    q8 = run.quantize()
+    for role in range(3):
+        xq, sc = fps.quantize_tiles(run.shape, run.raster[role], role, raster=True)
+        assert torch.equal(xq, q8[role][0]) and torch.equal(sc, q8[role][1])
+    for prec in (fps.PREC_FP8, fps.PREC_BF16):
+        for dt in (torch.float32, torch.bfloat16):
+            tiled = run.attn(prec, out_dtype=dt)
+            raster = run.attn(prec, out_dtype=dt, raster_out=True)
+            assert raster.shape == (1, 2) + tuple(grid) + (128,)
+            assert torch.equal(raster, fps.tile_unorder(run.shape, tiled))
 
 
 def test_two_runs_are_bit_identical(tiny):
