@@ -434,80 +434,99 @@ void attn_fp8_kernel(AttnArgs a) {
 // ---------------------------------------------------------------------------------------------
 // BF16: no quantisation.  K Q^T on v_mfma_f32_16x16x32_bf16; P is rounded to fp16 and multiplied
 // with the fp16 V tiles (exact per-tile power-of-two scaling, undone by s^V) on
-// v_mfma_f32_16x16x32_f16.
+// v_mfma_f32_16x16x32_f16.  Same in-wave pipeline as the FP8 kernel (PV one tile late, QK one tile
+// early).  A bf16 tile pair is 64 KB, so K and V are single-buffered: K(i+1) streams in during
+// phase 1 (after every wave has finished reading K(i)), V(i) during phase 2 (after every wave has
+// finished PV(i-1)); two barriers per iteration.
 // ---------------------------------------------------------------------------------------------
 union Bf16x8 { uint4 u; v8bf v; v8h h; };
 
 template <int TS>
-__global__ __launch_bounds__(TS * 2) void attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(TS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_bf16_kernel(AttnArgs a) {
     constexpr int NB = TS / 16;
     constexpr int NKK = TS / 32;
     constexpr int NTHR = TS * 2;
-    __shared__ __attribute__((aligned(16))) uint8_t ldsK[TS * 256];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsV[TS * 256];
+    constexpr int TILE_BYTES = TS * 256;
+    constexpr int CPT = (TS * 16) / NTHR;                  // 16-byte chunks per thread per operand tile (8)
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2][TILE_BYTES];   // K, V
     int bh, u;
     if (!work_item(a, &bh, &u)) return;
     const Geom& G = a.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
     const size_t tile0 = (size_t)bh * G.M;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(&lds[0][0]);
 
     Bf16x8 qop[2][4];
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.f, 0.f};
+    float alpha_prev[2] = {1.f, 1.f};
+    v4f acc[2][8];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wave * 32 + qb * 16 + n;
         const uint4* p = reinterpret_cast<const uint4*>(a.q + ((tile0 + u) * TS + row) * 256);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qop[qb][ks].u = p[ks * 4 + g];
-    }
-
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};
-    v4f acc[2][8];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
-
-    const int t0 = max(0, ut - a.rt), t1 = min(G.nT - 1, ut + a.rt);
-    const int h0 = max(0, uh - a.rh), h1 = min(G.nH - 1, uh + a.rh);
-    const int w0 = max(0, uw - a.rw), w1 = min(G.nW - 1, uw + a.rw);
-    const uint4* ldsK4 = reinterpret_cast<const uint4*>(ldsK);
-    const uint4* ldsV4 = reinterpret_cast<const uint4*>(ldsV);
+    }
     const float sc = kLog2eOverSqrtD;
 
-    for (int vt = t0; vt <= t1; ++vt)
-    for (int vh = h0; vh <= h1; ++vh)
-    for (int vw = w0; vw <= w1; ++vw) {
-        const int v = (vt * G.nH + vh) * G.nW + vw;
-        __syncthreads();
-        {
-            const uint4* gk = reinterpret_cast<const uint4*>(a.k + (tile0 + v) * TS * 256);
-            const uint4* gv = reinterpret_cast<const uint4*>(a.v + (tile0 + v) * TS * 256);
-            for (int c = tid; c < TS * 16; c += NTHR) {
-                reinterpret_cast<uint4*>(ldsK)[c] = gk[c];
-                reinterpret_cast<uint4*>(ldsV)[c] = gv[c];
-            }
-        }
-        __syncthreads();
-        const int cls = tile_class(G, vt, vh, vw);
-        const float svv = a.sv[tile0 + v];
-        if (a.visited && bh == 0 && tid == 0) a.visited[(size_t)u * G.M + v] = 1;
+    TileWalk w0, w1;                                       // tile i and tile i+1
+    w0.init(a, ut, uh, uw);
+    w1 = w0;
+    w1.next();
+    const int ntiles = w0.n;
+    auto tile_of = [&](const TileWalk& w) { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) {
+        const int chunk0 = c * NTHR + wave * 64;           // wave-uniform
+        dma_chunk(reinterpret_cast<const uint4*>(src) + chunk0 + lane,
+                  lds_base + buf * TILE_BYTES + chunk0 * 16);
+    };
+    auto k_tile = [&](int v) { return a.k + (tile0 + v) * TILE_BYTES; };
+    auto v_tile = [&](int v) { return a.v + (tile0 + v) * TILE_BYTES; };
+    const uint4* ldsK4 = reinterpret_cast<const uint4*>(lds[0]);
+    const uint4* ldsV4 = reinterpret_cast<const uint4*>(lds[1]);
 
-        v4f s[2][NB];
+    v4f s[2][NB];
+    Bf16x8 pop[2][NKK];                                    // P^T in fp16, 8 keys per operand
+
+    auto qk_block = [&](int b) {                           // S(b) = K(b) Q^T, both query blocks
+        Bf16x8 kop[4];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            s[0][b] = v4f{0.f, 0.f, 0.f, 0.f};
-            s[1][b] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < 4; ++ks) kop[ks].u = ldsK4[(b * 4 + ks) * 64 + lane];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                Bf16x8 kop;
-                kop.u = ldsK4[(b * 4 + ks) * 64 + lane];
+        for (int qb = 0; qb < 2; ++qb) {
+            v4f r = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    s[qb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop.v, qop[qb][ks].v, s[qb][b], 0, 0, 0);
-            }
+            for (int ks = 0; ks < 4; ++ks)
+                r = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks].v, qop[qb][ks].v, r, 0, 0, 0);
+            s[qb][b] = r;
         }
+    };
+    auto pv_block = [&](int cb, v4f (&t)[2]) {             // V^T(cb) P^T, raw, both query blocks
+        Bf16x8 vop[NKK];
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) vop[kk].u = ldsV4[(kk * 8 + cb) * 64 + lane];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            v4f r = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk)
+                r = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop[kk].h, pop[qb][kk].h, r, 0, 0, 0);
+            t[qb] = r;
+        }
+    };
+    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            acc[qb][cb] += t[qb] * svv;
+            asm volatile("" : "+v"(acc[qb][cb]));
+        }
+    };
+    auto mask_scores = [&](int cls) {
         if ((a.partial_cls >> cls) & 1u) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -517,50 +536,128 @@ __global__ __launch_bounds__(TS * 2) void attn_bf16_kernel(AttnArgs a) {
                     if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
             }
         }
-
-        Bf16x8 pop[2][NKK];
+    };
+    auto rescale_acc = [&]() {
+        if (__any(alpha_prev[0] != 1.0f || alpha_prev[1] != 1.0f)) {
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            float mx = s[qb][0][0];
+            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) mx = __builtin_fmaxf(mx, s[qb][b][r]);
-            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
-            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(mx * sc));
-            const float alpha = fast_exp2(m_run[qb] - m_new);
-            m_run[qb] = m_new;
-            float rs = 0.f;
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float p[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, -m_new));
-                    rs += p[r];
-                }
-#pragma unroll
-                for (int r = 0; r < 4; ++r) pop[qb][b >> 1].h[(b & 1) * 4 + r] = (_Float16)p[r];
-            }
-            l_run[qb] = l_run[qb] * alpha + rs;
-#pragma unroll
-            for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= alpha;
+                for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= alpha_prev[qb];
         }
+    };
 
+    // prologue: K(0) staged, S(0) computed
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) stage_chunk(0, k_tile(tile_of(w0)), c);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < NB; ++b) qk_block(b);
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
+
+    float svv_prev = 0.f;
+    auto iteration = [&](auto first_tag, auto last_tag) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        constexpr bool LAST = decltype(last_tag)::value;
+        const int v = tile_of(w0);
+        const float svv = load_uniform(a.sv, tile0 + v);
+        if (a.visited && bh == 0 && tid == 0) a.visited[(size_t)u * G.M + v] = 1;
+        const uint8_t* ksrc = LAST ? nullptr : k_tile(tile_of(w1));
+        const uint8_t* vsrc = v_tile(v);
+        __syncthreads();                 // every wave has finished QK(i): the K buffer is free; V(i-1) visible
+
+        // ---- phase 1: row maxima of S(i)  |  delayed PV(i-1)  |  K(i+1) streams in ------------
+        if (!FIRST) rescale_acc();
+        float mx[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+            mx[qb] = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
+                                     __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) {
-            v4f t[2] = {v4f{0.f, 0.f, 0.f, 0.f}, v4f{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-            for (int kk = 0; kk < NKK; ++kk) {
-                Bf16x8 vop;
-                vop.u = ldsV4[(kk * 8 + cb) * 64 + lane];
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    t[qb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop.h, pop[qb][kk].h, t[qb], 0, 0, 0);
+            if (!FIRST) {
+                v4f tq[2];
+                pv_block(cb, tq);
+                pv_accumulate(cb, tq, svv_prev);
             }
-            acc[0][cb] += t[0] * svv;
-            acc[1][cb] += t[1] * svv;
+            if (cb >= 1 && cb < NB) {
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    mx[qb] = __builtin_fmaxf(__builtin_fmaxf(mx[qb], s[qb][cb][0]), s[qb][cb][1]);
+                    mx[qb] = __builtin_fmaxf(__builtin_fmaxf(mx[qb], s[qb][cb][2]), s[qb][cb][3]);
+                }
+            }
+            if (!LAST && cb < CPT) stage_chunk(0, ksrc, cb);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        static_assert(CPT <= 8, "K staging is spread over the 8 channel blocks of phase 1");
+        float cm[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float t = mx[qb];
+            t = __builtin_fmaxf(t, __shfl_xor(t, 16));
+            t = __builtin_fmaxf(t, __shfl_xor(t, 32));
+            const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(t * sc));
+            alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
+            m_run[qb] = m_new;
+            cm[qb] = -m_new;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // K(i+1): this thread's share landed
+        __syncthreads();                 // every wave has finished PV(i-1): the V buffer is free; K(i+1) visible
+
+        // ---- phase 2: P(i) in fp16  |  early QK(i+1)  |  V(i) streams in -----------------------
+        float rs[2] = {0.f, 0.f};
+        constexpr int DMA_PER_BLOCK = (CPT + NB - 1) / NB;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                _Float16 ph[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float p = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm[qb]));
+                    rs[qb] += p;
+                    ph[r] = (_Float16)p;
+                }
+                v2h lo = v2h{ph[0], ph[1]}, hi = v2h{ph[2], ph[3]};
+                uint32_t wlo = __builtin_bit_cast(uint32_t, lo), whi = __builtin_bit_cast(uint32_t, hi);
+                asm volatile("" : "+v"(wlo), "+v"(whi), "+v"(rs[qb]));   // keep the pass in place
+                uint32_t* dstw = reinterpret_cast<uint32_t*>(&pop[qb][b >> 1].u);
+                dstw[(b & 1) * 2 + 0] = wlo;
+                dstw[(b & 1) * 2 + 1] = whi;
+            }
+            if (!LAST) qk_block(b);
+#pragma unroll
+            for (int c = b * DMA_PER_BLOCK; c < (b + 1) * DMA_PER_BLOCK && c < CPT; ++c)
+                stage_chunk(1, vsrc, c);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
+        w0.next();
+        w1.next();
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
+        svv_prev = svv;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // V(i): this thread's share landed
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    if (ntiles == 1) {
+        iteration(T_{}, T_{});
+    } else {
+        iteration(T_{}, F_{});
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{});
+        iteration(F_{}, T_{});
+    }
+    // epilogue: the last tile's PV
+    __syncthreads();
+    rescale_acc();
+    {
+        v4f tq[2];
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+            pv_block(cb, tq);
+            pv_accumulate(cb, tq, svv_prev);
         }
     }
 
