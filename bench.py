@@ -40,6 +40,10 @@ def main():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense BF16 / dense FP8 reference runs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the timed CPU oracle sample")
     ap.add_argument("--cpu-heads", type=int, default=4, help="heads in the timed CPU oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference for the profiler's traffic counters)")
+    ap.add_argument("--schedule", action="store_true",
+                    help="also run the 50-call denoising-step-aware schedule (Eq. 6) on fresh inputs per call")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads shard across GPUs without any "
@@ -84,6 +88,12 @@ def main():
         if events:
             events[2].record()
 
+    if args.copy_calibration:
+        a_ = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        b_ = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        fps.debug_copy(a_, b_)
+        torch.cuda.synchronize()
+        del a_, b_
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -149,10 +159,81 @@ def main():
         result["speedup_vs_own_dense_bf16"] = {"attention_only": bf16_ms / attn_ms,
                                                "with_quantize": bf16_ms / (attn_ms + quant_ms)}
 
+    if args.schedule:
+        del raster
+        result["schedule"] = run_schedule(w, shape, dev)
+
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_heads, TS)
 
     print(json.dumps(result))
+
+
+def run_schedule(w, shape, dev, num_steps=50, alpha1=0.2, alpha2=0.5):
+    """Denoising-step-aware schedule (Eq. 6) with the thresholds t1 = 0.2 D, t2 = 0.5 D, D = 50: calls
+    1-10 dense BF16, 11-25 FP8 with a 7x5x5-tile window, 26-50 FP8 with a 3x3x3-tile window, every
+    call on its own seed-generated Q, K, V (all 50 sets resident in HBM before the clock starts).
+    Each call runs the whole path for its regime: FP8 = fused tile-order+quantise x3 + attention;
+    BF16 = tile order x3 + operand packing x3 + attention.  The regime is picked by the library from
+    the step configuration passed to fps_attn_fwd."""
+    import torch
+    from paper_2506_04648_amd import fps, synth
+    dense_win = tuple(2 * (-(-g // t)) - 1 for g, t in zip(w.grid, w.tile))
+    regimes = [(fps.PREC_BF16, dense_win), (fps.PREC_FP8, (7, 5, 5)), (fps.PREC_FP8, (3, 3, 3))]
+    TS = w.tile[0] * w.tile[1] * w.tile[2]
+    t0 = time.time()
+    inputs = []
+    for call in range(num_steps):
+        q, k, v = synth.qkv_raster(w, call_index=call, workers=min(16, os.cpu_count() or 1))
+        inputs.append([torch.from_numpy(a[None]).to(dev).to(torch.bfloat16) for a in (q, k, v)])
+        del q, k, v
+    gen_s = time.time() - t0
+    M = fps.num_tiles(shape)
+    L = M * TS
+    packed8 = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device=dev) for _ in range(3)]
+    packed16 = [torch.empty(fps.packed_bytes(shape, fps.PREC_BF16), dtype=torch.uint8, device=dev) for _ in range(3)]
+    tiled = [torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+    scales = [torch.empty((1, w.heads, M), dtype=torch.float32, device=dev) for _ in range(3)]
+    out = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.bfloat16, device=dev)
+
+    def call_step(step):
+        cfg = fps.make_step_cfg(step, num_steps, alpha1, alpha2, regimes)
+        prec, _ = fps.schedule_select(cfg)
+        x = inputs[step - 1]
+        if prec == fps.PREC_FP8:
+            for i in range(3):
+                fps.quantize_tiles(shape, x[i], i, out=packed8[i], scales=scales[i], raster=True)
+            fps.attn_fwd(shape, None, prec, packed8[0], packed8[1], packed8[2], scales[0], scales[1],
+                         scales[2], out=out, raster_out=True, step=cfg)
+        else:
+            for i in range(3):
+                fps.tile_order(shape, x[i], out=tiled[i])
+                fps.pack_tiles_bf16(shape, tiled[i], i, out=packed16[i], vscale=scales[2])
+            fps.attn_fwd(shape, None, prec, packed16[0], packed16[1], packed16[2], sv=scales[2], out=out,
+                         raster_out=True, step=cfg)
+        return prec
+
+    call_step(1); call_step(11); call_step(26)                 # warm-up of the three regimes
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(num_steps + 1)]
+    t0 = time.perf_counter()
+    marks[0].record()
+    for step in range(1, num_steps + 1):
+        call_step(step)
+        marks[step].record()
+    torch.cuda.synchronize()
+    total_ms = (time.perf_counter() - t0) * 1e3
+    per_call = [marks[i].elapsed_time(marks[i + 1]) for i in range(num_steps)]
+    res = {"num_steps": num_steps, "alpha": [alpha1, alpha2], "total_ms": total_ms, "input_gen_s": round(gen_s, 1),
+           "regimes": []}
+    bounds = [(0, 10, "dense BF16"), (10, 25, "FP8 window 7x5x5"), (25, 50, "FP8 window 3x3x3")]
+    for (lo, hi, name), (prec, win) in zip(bounds, regimes):
+        pairs, _ = kept_pairs(w.grid, w.tile, win)
+        flop = pairs * w.heads * 4.0 * TS * TS * w.head_dim
+        ms = sum(per_call[lo:hi]) / (hi - lo)
+        res["regimes"].append({"calls": hi - lo, "mode": name, "window_tiles": list(win), "kept_tile_pairs": pairs,
+                               "ms_per_call": ms, "tflops_whole_path": flop / ms / 1e9})
+    return res
 
 
 def cpu_baseline(w, n_heads, TS):

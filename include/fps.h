@@ -144,6 +144,11 @@ int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_ro
 int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,
                         uint8_t* codes_rowmajor, void* stream);
 
+/* Debug: plain device-to-device copy of `bytes` bytes (a positive multiple of 16; src and dst are
+ * device memory and must not overlap).  A kernel of exactly known HBM traffic, used to calibrate
+ * the profiler's FETCH_SIZE / WRITE_SIZE counters. */
+int fps_debug_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Debug: the raw score accumulators sum_c qcode_ic * kcode_jc (before the s^Q s^K / sqrt(d)
  * dequantisation of Eq. 3) of query tile u and key tile v of head bh, computed with the same
  * matrix instruction as fps_attn_fwd; `scores` is device memory of TS*TS floats, [query][key]

@@ -43,6 +43,7 @@ struct AttnArgs {
 
 constexpr float kLog2eOverSqrtD = 0.12751743f;   // log2(e) / sqrt(128)
 constexpr float kLog2Of448 = 8.8073549f;          // log2(448)
+constexpr int kStoreRegionBytes = 16 * (512 + 16);  // per-wave LDS region of the output transpose
 
 // Scales are read-only for the whole launch and indexed uniformly: reading them through the constant
 // address space lets the compiler use scalar loads, which do not queue behind the vector-memory
@@ -75,46 +76,62 @@ __device__ __forceinline__ int tile_class(const Geom& g, int t, int h, int w) {
     return ((t == g.nT - 1) << 2) | ((h == g.nH - 1) << 1) | (w == g.nW - 1);
 }
 
-// Epilogue shared by both precisions: O = acc * inv_l, padded rows zero, fp32 or bf16 store.
+// Epilogue shared by both precisions: O = acc * inv_l (times the per-channel V scale if any),
+// padded rows zero, fp32 or bf16, tile or raster order.  A lane holds 4 channels of one row per
+// accumulator, so direct stores would be 8- or 16-byte pieces of many rows; instead each wave
+// transposes its 16-row blocks through a private 16 KB LDS region and writes whole rows
+// (256 or 512 contiguous bytes).  The caller guarantees that no wave still reads the LDS buffers.
 template <int TS>
 __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int ucls, int wave,
-                                           int g, int n, const v4f (&acc)[2][8], const float (&inv)[2],
-                                           const float* ch_scale = nullptr) {
+                                           int lane, const v4f (&acc)[2][8], const float (&inv)[2],
+                                           uint8_t* wave_lds, const float* ch_scale = nullptr) {
+    const Geom& G = a.g;
+    const int g = lane >> 4, n = lane & 15;
+    const int row_bytes = a.out_f32 ? 512 : 256;
+    const int pitch = row_bytes + 16;                      // padding keeps the column writes off one bank
+    const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const int rr = wave * 32 + qb * 16 + n;
-        const bool valid = (a.g.valid_mask[ucls][rr >> 5] >> (rr & 31)) & 1u;
-        const float sc = valid ? inv[qb] : 0.0f;
-        size_t row = ((size_t)bh * a.g.M + u) * TS + rr;
-        if (a.out_raster) {                                // token (t,h,w) of in-tile rank rr
-            if (!valid) continue;
-            const Geom& G = a.g;
-            const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
-            const int rw = rr % G.Tw, rh = (rr / G.Tw) % G.Th, rt = rr / (G.Tw * G.Th);
-            row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
-        }
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) {
             const int col = 16 * cb + 4 * g;
-            v4f o = acc[qb][cb] * sc;
+            v4f o = acc[qb][cb] * inv[qb];
             if (ch_scale) o *= *reinterpret_cast<const v4f*>(ch_scale + col);
-            if (!valid) o = v4f{0.f, 0.f, 0.f, 0.f};
             if (a.out_f32) {
-                *reinterpret_cast<v4f*>(reinterpret_cast<float*>(a.out) + row * 128 + col) = o;
+                *reinterpret_cast<v4f*>(wave_lds + n * pitch + col * 4) = o;
             } else {
                 uint2 pk;
                 pk.x = f32_to_bf16_bits(o[0]) | (f32_to_bf16_bits(o[1]) << 16);
                 pk.y = f32_to_bf16_bits(o[2]) | (f32_to_bf16_bits(o[3]) << 16);
-                *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + row * 128 + col) = pk;
+                *reinterpret_cast<uint2*>(wave_lds + n * pitch + col * 2) = pk;
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // whole rows: 16 lanes (bf16) or 32 lanes (fp32) per row, 16 bytes per lane
+        const int lanes_per_row = row_bytes / 16;
+        const int rows_per_pass = 64 / lanes_per_row;
+        for (int r0 = 0; r0 < 16; r0 += rows_per_pass) {
+            const int r = r0 + lane / lanes_per_row, chunk = lane % lanes_per_row;
+            const int rr = wave * 32 + qb * 16 + r;        // in-tile rank of the row
+            const bool valid = (G.valid_mask[ucls][rr >> 5] >> (rr & 31)) & 1u;
+            uint4 val = *reinterpret_cast<const uint4*>(wave_lds + r * pitch + chunk * 16);
+            size_t row;
+            if (a.out_raster) {
+                if (!valid) continue;
+                const int rw = rr % G.Tw, rh = (rr / G.Tw) % G.Th, rt = rr / (G.Tw * G.Th);
+                row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
+            } else {
+                row = ((size_t)bh * G.M + u) * TS + rr;
+                if (!valid) val = make_uint4(0, 0, 0, 0);
+            }
+            reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) + row * row_bytes)[chunk] = val;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();                   // the region is reused by the next block
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// FP8 E4M3: both products on v_mfma_f32_16x16x128_f8f6f4 (TS = 128) or, for the PV product of
-// 32-token tiles, v_mfma_f32_16x16x32_fp8_fp8.
-// ---------------------------------------------------------------------------------------------
 // Walks the key-tile box of Eq. 2 in (t, h, w) order.
 struct TileWalk {
     int t0, h0, w0, h1, w1;
@@ -427,8 +444,9 @@ void attn_fp8_kernel(AttnArgs a) {
         l += __shfl_xor(l, 32);
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
-    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, g, n, acc, inv,
-                   VCH ? a.sv + (size_t)bh * 128 : nullptr);
+    __syncthreads();                                       // all waves are done with the staged tiles
+    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+                   &lds[0][0] + wave * kStoreRegionBytes, VCH ? a.sv + (size_t)bh * 128 : nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -669,7 +687,9 @@ void attn_bf16_kernel(AttnArgs a) {
         l += __shfl_xor(l, 32);
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;
     }
-    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, g, n, acc, inv);
+    __syncthreads();                                       // all waves are done with the staged tiles
+    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+                   &lds[0][0] + wave * kStoreRegionBytes);
 }
 
 // Debug: raw E4M3 score accumulators sum_c q_ic * k_jc of one tile pair, produced by the same MFMA

@@ -225,6 +225,16 @@ int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,
     return launch_unpack_q8(g, xq, role, codes_rowmajor, (hipStream_t)stream);
 }
 
+int fps_debug_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    FPS_TRY(check_ptr(src, "src"));
+    FPS_TRY(check_ptr(dst, "dst"));
+    if (bytes == 0 || (bytes & 15u) || bytes > ((size_t)1 << 40)) {
+        set_error("bytes must be a positive multiple of 16");
+        return FPS_ERR_INVALID_ARG;
+    }
+    return launch_copy(src, dst, (long long)bytes, (hipStream_t)stream);
+}
+
 int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u, int v,
                         float* scores, void* stream) {
     Geom g;

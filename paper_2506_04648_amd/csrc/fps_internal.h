@@ -38,6 +38,7 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
                 const void* v, const float* sq, const float* sk, const float* sv, int vscale,
                 void* out, int out_f32, int out_raster, uint8_t* visited, hipStream_t st);
 
+int launch_copy(const void* in, void* out, long long bytes, hipStream_t st);
 int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int v, float* out,
                       hipStream_t st);
 

@@ -153,6 +153,12 @@ __global__ __launch_bounds__(256) void unpack_q8_kernel(const uint8_t* __restric
     }
 }
 
+// ---- plain copy (calibration of HBM traffic counters against a kernel of known size) ------------
+__global__ void copy_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, long long n_chunks) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_chunks) out[i] = in[i];
+}
+
 static inline int grid_for(long long n, int block) { return (int)((n + block - 1) / block); }
 
 int launch_tile_order(const Geom& g, const void* in, void* out, hipStream_t st) {
@@ -168,6 +174,13 @@ int launch_tile_unorder(const Geom& g, const void* in, int elem_bytes, void* out
     tile_unorder_kernel<<<grid_for(n, 256), 256, 0, st>>>((const uint4*)in, (uint4*)out, g, cpr, n);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "tile_unorder launch");
+}
+
+int launch_copy(const void* in, void* out, long long bytes, hipStream_t st) {
+    const long long n = bytes / 16;
+    copy_kernel<<<grid_for(n, 256), 256, 0, st>>>((const uint4*)in, (uint4*)out, n);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "copy launch");
 }
 
 int launch_pack_bf16(const Geom& g, const void* x, int role, void* xp, float* vscale, hipStream_t st) {

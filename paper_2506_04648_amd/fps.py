@@ -26,7 +26,8 @@ LAYOUT_TILED, LAYOUT_RASTER = 0, 1
 EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_packed_bytes",
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
            "fps_quantize_raster",
-           "fps_pack_tiles_bf16", "fps_debug_unpack_q8", "fps_debug_scores_q8", "fps_attn_fwd")
+           "fps_pack_tiles_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
+           "fps_attn_fwd")
 
 
 class Shape(ctypes.Structure):
@@ -79,6 +80,7 @@ def lib():
         L.fps_quantize_raster.argtypes = [ctypes.POINTER(Shape), vp, ip, ip, vp, vp, vp]
         L.fps_pack_tiles_bf16.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp, vp]
         L.fps_debug_unpack_q8.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp]
+        L.fps_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fps_debug_scores_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, vp, vp]
         L.fps_attn_fwd.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), ip,
                                    ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, ip, vp, vp]
@@ -216,6 +218,14 @@ def debug_unpack_q8(shape: Shape, xq, role):
     return out
 
 
+def debug_copy(src, dst):
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(lib().fps_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream()))
+    return dst
+
+
 def debug_scores_q8(shape: Shape, q8, k8, bh, u, v):
     import torch
     ts = shape.Tt * shape.Th * shape.Tw
@@ -235,6 +245,8 @@ def attn_fwd(shape: Shape, window, prec, q, k, v, sq=None, sk=None, sv=None, vsc
         out = torch.empty((shape.B, shape.heads) + dims, dtype=out_dtype, device=q.device)
     dt = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
     win = Window(*window) if window is not None else None
+    if win is None and step is None:
+        raise ValueError("attn_fwd needs a window or a step configuration")
     _check(lib().fps_attn_fwd(ctypes.byref(shape), ctypes.byref(win) if win is not None else None,
                               prec, ctypes.byref(step) if step is not None else None,
                               _ptr(q), _ptr(k), _ptr(v), _ptr(sq), _ptr(sk), _ptr(sv), vscale,

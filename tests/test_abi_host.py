@@ -106,6 +106,8 @@ def test_device_entry_points_validate_before_launching():
     assert L.fps_attn_fwd(S, ctypes.byref(win), 1, None, good, good, good, good, good, good, 0,
                           good, 1, 2, None, None) == fps.FPS_ERR_INVALID_ARG   # bad output layout
     assert L.fps_quantize_raster(S, good, 0, 0, None, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_debug_copy(good, good, 24, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_debug_copy(good, None, 32, None) == fps.FPS_ERR_INVALID_ARG
     big = fps.make_shape(2, (4, 16, 16), (2, 8, 4))                             # 64-token tiles
     assert L.fps_attn_fwd(ctypes.byref(big), ctypes.byref(win), 1, None, *args) == fps.FPS_ERR_UNSUPPORTED
     cfg = fps.make_step_cfg(99, 50, 0.2, 0.5, [(1, (3, 3, 3))] * 3)
