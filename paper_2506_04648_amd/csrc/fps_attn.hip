@@ -158,13 +158,19 @@ __device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
 // wave deposits its chunk at lds_wave_base + 16 i.  Written as inline assembly so that the
 // compiler's wait-count bookkeeping does not serialise it against LDS reads of OTHER buffers; the
 // kernel waits for it explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
-__device__ __forceinline__ void dma_chunk(const void* gsrc_lane, uint32_t lds_wave_base) {
-    lds_wave_base = __builtin_amdgcn_readfirstlane(lds_wave_base);   // wave-uniform by construction
-    asm volatile("s_mov_b32 m0, %1\n\t"
+// gsrc is a wave-uniform base (kept in scalar registers), lane_off the lane's byte offset from it.
+__device__ __forceinline__ void dma_chunk(const void* gsrc, uint32_t lane_off, uint32_t lds_wave_base) {
+    // both are wave-uniform by construction; say so where the compiler cannot prove it
+    const uint64_t p = reinterpret_cast<uint64_t>(gsrc);
+    gsrc = reinterpret_cast<const void*>(
+        (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p) |
+        ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32)) << 32));
+    lds_wave_base = __builtin_amdgcn_readfirstlane(lds_wave_base);
+    asm volatile("s_mov_b32 m0, %2\n\t"
                  "s_nop 0\n\t"
-                 "global_load_lds_dwordx4 %0, off"
+                 "global_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(gsrc_lane), "s"(lds_wave_base)
+                 : "v"(lane_off), "s"(gsrc), "s"(lds_wave_base)
                  : "memory", "m0");
 }
 
@@ -216,10 +222,10 @@ void attn_fp8_kernel(AttnArgs a) {
     auto tile_of = [&](const TileWalk& w) { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
 
     // chunk c (of CPT) of this thread's share of one operand tile, HBM -> lds[buf]
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the wave index, in a scalar register
     auto stage_chunk = [&](int buf, const uint8_t* src, int c) {
-        const int chunk0 = c * NTHR + wave * 64;           // wave-uniform
-        dma_chunk(reinterpret_cast<const uint4*>(src) + chunk0 + lane,
-                  lds_base + buf * TILE_BYTES + chunk0 * 16);
+        dma_chunk(src + c * NTHR * 16, tid * 16,
+                  lds_base + buf * TILE_BYTES + (c * NTHR + wave_s * 64) * 16);
     };
     auto stage = [&](int buf, const uint8_t* src) {
 #pragma unroll
@@ -397,7 +403,7 @@ void attn_fp8_kernel(AttnArgs a) {
                     p[r] = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm[qb]));
                     rs[qb] += p[r];
                 }
-                int pw = 0;
+                int pw = pb[qb][b];                        // both halves are overwritten below
                 pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], pw, false);
                 pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], pw, true);
                 // pinned here: otherwise the compiler sinks the whole exponential pass below the
@@ -498,10 +504,10 @@ void attn_bf16_kernel(AttnArgs a) {
     w1.next();
     const int ntiles = w0.n;
     auto tile_of = [&](const TileWalk& w) { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the wave index, in a scalar register
     auto stage_chunk = [&](int buf, const uint8_t* src, int c) {
-        const int chunk0 = c * NTHR + wave * 64;           // wave-uniform
-        dma_chunk(reinterpret_cast<const uint4*>(src) + chunk0 + lane,
-                  lds_base + buf * TILE_BYTES + chunk0 * 16);
+        dma_chunk(src + c * NTHR * 16, tid * 16,
+                  lds_base + buf * TILE_BYTES + (c * NTHR + wave_s * 64) * 16);
     };
     auto k_tile = [&](int v) { return a.k + (tile0 + v) * TILE_BYTES; };
     auto v_tile = [&](int v) { return a.v + (tile0 + v) * TILE_BYTES; };
