@@ -319,12 +319,17 @@ def test_wan_1_3b_480p_fp8_sampled():
     run, pairs = _sampled_parity(synth.WAN_1_3B_480P, fps.PREC_FP8, synth.WAN_1_3B_480P.window,
                                  [0, 5, 11], seed=1)
     assert pairs == 6100
-    # scales of every head, bit exact
+    # scales of every head and codes of one head per tensor, bit exact
     for role, (xq, sc) in enumerate(run.q8):
         sc = sc[0].cpu().numpy()
         for h in range(run.w.heads):
             ws = fo.tile_scales(fo.tile_order(run.qkv[role][h], run.g), run.g)
             assert np.array_equal(sc[h], ws)
+        h = (5, 0, 11)[role]
+        codes = fps.debug_unpack_q8(run.shape, xq, role)[0, h].cpu().numpy()
+        wc, _ = fo.quantize_tiles(fo.tile_order(run.qkv[role][h].astype(np.float64), run.g), run.g)
+        zero_sign = ((codes ^ wc) == 0x80) & ((wc & 0x7F) == 0)
+        assert int(((codes != wc) & ~zero_sign).sum()) == 0, (role, h)
 
 
 def test_wan_1_3b_480p_bf16_sparse_sampled():
