@@ -20,6 +20,9 @@ if ROOT not in sys.path:
 
 FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
 BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the attention kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a
+# plain 1 GiB copy kernel (profiles/attn_fp8_wan14b-720p_counters.md); measured, not computed here.
+MEASURED_TRAFFIC_BYTES = {"wan14b-720p": 3.84e9}
 
 
 def kept_pairs(grid, tile, window):
@@ -123,7 +126,9 @@ def main():
         "quantize_GBps": 3.0 * 3 * w.heads * L * 128 / (quant_ms * 1e-3) / 1e9,
         "roofline": {"bound": "mfma", "kernel": "attn_fp8_kernel", "achieved": flop / (attn_ms * 1e-3) / 1e12,
                      "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flop / (attn_ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, "traffic": None},
+                     "frac": flop / (attn_ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "algorithmic_bytes": 3.0 * w.heads * L * 128 + 2.0 * w.heads * w.grid[0] * w.grid[1] * w.grid[2] * 128},
         "paper_context": {"kernel_speedup_vs_bf16_H20": 7.09, "e2e_speedup_vs_bf16_H20": 4.96},
     }
 
