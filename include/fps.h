@@ -66,10 +66,18 @@ typedef struct {
     int Tt, Th, Tw;           /* tile; the padded grid is the grid rounded up to tile multiples   */
 } fps_shape;
 
-/* Window in tiles (Eq. 2): key tile v is kept for query tile u iff |u_a - v_a| <= w_a/2 (integer
- * division) on each axis a; ranges are truncated at the grid boundary.  An even w_a therefore
- * keeps the same tiles as w_a + 1, and w_a >= 2*n_a - 1 keeps the whole axis (dense). */
-typedef struct { int wt, wh, ww; } fps_window;
+typedef enum {
+    FPS_EDGE_TRUNCATE = 0,  /* Eq. 2 as a pure distance test: edge tiles see fewer key tiles      */
+    FPS_EDGE_SHIFT = 1      /* the window centre is clamped to [r_a, n_a-1-r_a] on each axis, so
+                               every query tile sees min(2 r_a + 1, n_a) key tiles per axis       */
+} fps_edge;
+
+/* Window in tiles (Eq. 2): with r_a = w_a/2 (integer division), key tile v is kept for query tile
+ * u iff |c_a - v_a| <= r_a on each axis a, where c_a = u_a (FPS_EDGE_TRUNCATE: ranges are cut at
+ * the grid boundary) or c_a = clamp(u_a, r_a, n_a-1-r_a) (FPS_EDGE_SHIFT; the whole axis if
+ * n_a <= 2 r_a + 1).  An even w_a keeps the same tiles as w_a + 1, and w_a >= 2*n_a - 1 keeps the
+ * whole axis (dense). */
+typedef struct { int wt, wh, ww; fps_edge edge; } fps_window;
 
 typedef struct { fps_precision prec; fps_window win; } fps_regime;
 

@@ -123,13 +123,31 @@ def tile_coords(g: Geometry) -> np.ndarray:
     return np.stack([ut.reshape(-1), uh.reshape(-1), uw.reshape(-1)], axis=1)
 
 
-def tile_mask(g: Geometry, window) -> np.ndarray:
+EDGE_TRUNCATE = 0   # Eq. 2 as a pure distance test: edge tiles keep fewer key tiles
+EDGE_SHIFT = 1      # the window centre is clamped into the grid: constant number of key tiles
+
+
+def tile_mask(g: Geometry, window, edge=None) -> np.ndarray:
     """bool [M, M]: keep[u, v] iff the Chebyshev-type box test of Eq. 2 holds on every axis,
-    with window sizes in tiles: |u_a - v_a| <= floor(w_a / 2)."""
+    with window sizes in tiles: |c_a - v_a| <= r_a = floor(w_a / 2).  The centre c is the query
+    tile itself (truncating edges, the literal Eq. 2), or with edge == EDGE_SHIFT the query tile
+    clamped to [r_a, n_a - 1 - r_a] so that the box never leaves the grid (an axis not longer than
+    the window is kept whole).  `window` may carry the edge rule as a fourth entry."""
+    if edge is None:
+        edge = window[3] if len(window) > 3 else EDGE_TRUNCATE
     c = tile_coords(g)
-    r = np.array([int(w) // 2 for w in window])
-    delta = np.abs(c[:, None, :] - c[None, :, :])
-    return np.all(delta <= r[None, None, :], axis=2)
+    keep = np.ones((g.M, g.M), dtype=bool)
+    for a, n in enumerate(g.n_tiles_axis):
+        r = int(window[a]) // 2
+        u, v = c[:, a][:, None], c[:, a][None, :]
+        if edge == EDGE_SHIFT:
+            if n <= 2 * r + 1:
+                continue                                   # the window covers the whole axis
+            centre = np.clip(u, r, n - 1 - r)
+        else:
+            centre = u
+        keep &= np.abs(centre - v) <= r
+    return keep
 
 
 # ----------------------------------------------------------------------------------------------

@@ -34,6 +34,7 @@ struct AttnArgs {
     uint8_t* visited;
     Geom g;
     int rt, rh, rw;        // window radii in tiles
+    int edge_shift;        // 1: clamp the window centre into the grid instead of truncating
     int out_f32;
     int out_raster;        // output in raster order (real tokens only) instead of tile order
     int chunk;             // work items per XCD
@@ -139,6 +140,12 @@ struct TileWalk {
     int n;                                  // number of tiles in the box
     __device__ __forceinline__ void init(const AttnArgs& a, int ut, int uh, int uw) {
         const Geom& G = a.g;
+        if (a.edge_shift) {                 // clamp the centre into [r, n-1-r]; an axis not longer than
+            // the window has no such centre and is kept whole by the truncation below with u = n/2
+            ut = G.nT > 2 * a.rt + 1 ? min(max(ut, a.rt), G.nT - 1 - a.rt) : G.nT / 2;
+            uh = G.nH > 2 * a.rh + 1 ? min(max(uh, a.rh), G.nH - 1 - a.rh) : G.nH / 2;
+            uw = G.nW > 2 * a.rw + 1 ? min(max(uw, a.rw), G.nW - 1 - a.rw) : G.nW / 2;
+        }
         t0 = max(0, ut - a.rt); h0 = max(0, uh - a.rh); w0 = max(0, uw - a.rw);
         const int t1 = min(G.nT - 1, ut + a.rt);
         h1 = min(G.nH - 1, uh + a.rh); w1 = min(G.nW - 1, uw + a.rw);
@@ -744,6 +751,7 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     a.out = out; a.visited = visited;
     a.g = g;
     a.rt = win.wt / 2; a.rh = win.wh / 2; a.rw = win.ww / 2;
+    a.edge_shift = win.edge == FPS_EDGE_SHIFT;
     a.out_f32 = out_f32;
     a.out_raster = out_raster;
     a.total = g.BH * g.M;

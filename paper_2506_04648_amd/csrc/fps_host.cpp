@@ -81,6 +81,10 @@ static int check_window(const fps_window* w) {
         set_error("window sizes must be positive");
         return FPS_ERR_INVALID_ARG;
     }
+    if (w->edge != FPS_EDGE_TRUNCATE && w->edge != FPS_EDGE_SHIFT) {
+        set_error("window.edge has invalid value %d", (int)w->edge);
+        return FPS_ERR_INVALID_ARG;
+    }
     return FPS_OK;
 }
 
@@ -141,15 +145,28 @@ int fps_tile_mask_host(const fps_shape* shape, const fps_window* win, uint8_t* m
     FPS_TRY(check_window(win));
     if (!mask) { set_error("mask is NULL"); return FPS_ERR_INVALID_ARG; }
     const int rt = win->wt / 2, rh = win->wh / 2, rw = win->ww / 2;
+    const bool shift = win->edge == FPS_EDGE_SHIFT;
+    // kept range [lo, hi] along one axis
+    auto lo_of = [shift](int u, int r, int n) {
+        if (!shift) return u - r > 0 ? u - r : 0;
+        if (n <= 2 * r + 1) return 0;
+        const int c = u < r ? r : (u > n - 1 - r ? n - 1 - r : u);
+        return c - r;
+    };
+    auto hi_of = [shift](int u, int r, int n) {
+        if (!shift) return u + r < n - 1 ? u + r : n - 1;
+        if (n <= 2 * r + 1) return n - 1;
+        const int c = u < r ? r : (u > n - 1 - r ? n - 1 - r : u);
+        return c + r;
+    };
     uint64_t pairs = 0;
     for (int u = 0; u < g.M; ++u) {
         const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
         for (int v = 0; v < g.M; ++v) {
             const int vw = v % g.nW, vh = (v / g.nW) % g.nH, vt = v / (g.nW * g.nH);
-            const int dt = ut > vt ? ut - vt : vt - ut;
-            const int dh = uh > vh ? uh - vh : vh - uh;
-            const int dw = uw > vw ? uw - vw : vw - uw;
-            const uint8_t keep = (dt <= rt && dh <= rh && dw <= rw) ? 1 : 0;
+            const uint8_t keep = (vt >= lo_of(ut, rt, g.nT) && vt <= hi_of(ut, rt, g.nT) &&
+                                  vh >= lo_of(uh, rh, g.nH) && vh <= hi_of(uh, rh, g.nH) &&
+                                  vw >= lo_of(uw, rw, g.nW) && vw <= hi_of(uw, rw, g.nW)) ? 1 : 0;
             mask[(size_t)u * g.M + v] = keep;
             pairs += keep;
         }

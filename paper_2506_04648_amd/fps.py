@@ -22,6 +22,7 @@ VSCALE_TILE, VSCALE_CHANNEL = 0, 1
 ROLE_Q, ROLE_K, ROLE_V = 0, 1, 2
 OUT_BF16, OUT_F32 = 0, 1
 LAYOUT_TILED, LAYOUT_RASTER = 0, 1
+EDGE_TRUNCATE, EDGE_SHIFT = 0, 1
 
 EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_packed_bytes",
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
@@ -35,7 +36,7 @@ class Shape(ctypes.Structure):
 
 
 class Window(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("wt", "wh", "ww")]
+    _fields_ = [(n, ctypes.c_int) for n in ("wt", "wh", "ww", "edge")]
 
 
 class Regime(ctypes.Structure):
@@ -105,7 +106,7 @@ def make_shape(heads, grid, tile, B=1, head_dim=128) -> Shape:
 
 
 def make_step_cfg(step, num_steps, alpha1, alpha2, regimes) -> StepCfg:
-    """regimes: three (prec, (wt, wh, ww)) pairs for the early, mid and late steps (Eq. 6)."""
+    """regimes: three (prec, (wt, wh, ww[, edge])) pairs for the early, mid and late steps (Eq. 6)."""
     cfg = StepCfg()
     cfg.step, cfg.num_steps, cfg.alpha1, cfg.alpha2 = step, num_steps, alpha1, alpha2
     for i, (prec, win) in enumerate(regimes):
@@ -127,6 +128,8 @@ def _ptr(t):
 def schedule_select(cfg: StepCfg):
     out = Regime()
     _check(lib().fps_schedule_select(ctypes.byref(cfg), ctypes.byref(out)))
+    if out.win.edge:
+        return out.prec, (out.win.wt, out.win.wh, out.win.ww, out.win.edge)
     return out.prec, (out.win.wt, out.win.wh, out.win.ww)
 
 

@@ -61,6 +61,9 @@ def test_tile_mask_host_matches_oracle(grid, tile, window):
     mask, pairs = fps.tile_mask_host(shape, window)
     want = fo.tile_mask(g, window)
     assert np.array_equal(mask.astype(bool), want) and pairs == int(want.sum())
+    mask_s, pairs_s = fps.tile_mask_host(shape, window + (fps.EDGE_SHIFT,))
+    want_s = fo.tile_mask(g, window, edge=fo.EDGE_SHIFT)
+    assert np.array_equal(mask_s.astype(bool), want_s) and pairs_s == int(want_s.sum())
     assert fps.packed_bytes(shape, fps.PREC_FP8) == 2 * g.L_padded * 128
     assert fps.packed_bytes(shape, fps.PREC_BF16) == 4 * g.L_padded * 128
 
@@ -98,6 +101,7 @@ def test_device_entry_points_validate_before_launching():
     assert L.fps_tile_unorder(S, good, 7, good, None) == fps.FPS_ERR_INVALID_ARG
     bad_win = fps.Window(0, 3, 3)
     args = (good, good, good, good, good, good, 0, good, 1, 0, None, None)
+    assert L.fps_attn_fwd(S, ctypes.byref(fps.Window(1, 3, 3, 2)), 1, None, *args) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_attn_fwd(S, ctypes.byref(bad_win), 1, None, *args) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_attn_fwd(S, ctypes.byref(win), 2, None, *args) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_attn_fwd(S, None, 1, None, *args) == fps.FPS_ERR_INVALID_ARG

@@ -209,6 +209,22 @@ def test_per_channel_v_scales(grid, tile, window):
         gu.assert_parity(st, f"per-channel V head {h}")
 
 
+@pytest.mark.parametrize("prec", [fps.PREC_FP8, fps.PREC_BF16])
+def test_shifted_window_edge_rule(prec):
+    say("shifted window", prec)
+    w = dataclasses.replace(synth.TINY, grid=(5, 13, 40), tile=(1, 8, 16), window=(3, 1, 3), heads=1,
+                            n_outlier=3, config_id=14)
+    run = gu.GpuRun(w)
+    win = w.window + (fps.EDGE_SHIFT,)
+    out, vis = run.attn(prec, window=win, visited=True)
+    mask = fo.tile_mask(run.g, win)
+    assert np.array_equal(vis.cpu().numpy().astype(bool), mask)
+    assert np.all(mask.sum(axis=1) == 3 * 1 * 3)
+    st = gu.compare_head(run, out, 0, prec, win)
+    say("  ", st)
+    gu.assert_parity(st, "shifted window")
+
+
 def test_shared_outlier_channels_stress():
     """Q and K share their outlier channels: the score spread is ~10x larger (|S'| ~ 100, rows
     close to one-hot), outside the input distribution the tolerances are stated for.  The error of

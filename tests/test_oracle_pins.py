@@ -90,6 +90,30 @@ def test_tile_mask_against_real_valued_centres(window):
             assert keep[iu, iv] == brute.in_window(tu, tv, window)
 
 
+@pytest.mark.parametrize("window", [(3, 3, 3), (5, 3, 1), (2, 7, 4), (9, 9, 99)])
+def test_shifted_window_keeps_a_constant_number_of_tiles(window):
+    g = fo.Geometry(7, 9, 10, 1, 2, 3)                       # 7 x 5 x 4 tiles
+    keep = fo.tile_mask(g, window, edge=fo.EDGE_SHIFT)
+    per_axis = [min(2 * (w // 2) + 1, n) for w, n in zip(window, g.n_tiles_axis)]
+    assert np.all(keep.sum(axis=1) == per_axis[0] * per_axis[1] * per_axis[2])
+    assert np.all(np.diag(keep))                             # a tile always sees itself
+    trunc = fo.tile_mask(g, window)
+    assert np.all(keep | ~trunc)                             # the truncated window is a subset
+    # explicit definition per axis: a contiguous run of fixed length that contains u and fits the grid
+    nT, nH, nW = g.n_tiles_axis
+    tiles = [(a, b, c) for a in range(nT) for b in range(nH) for c in range(nW)]
+    for iu, tu in enumerate(tiles):
+        for iv, tv in enumerate(tiles):
+            ok = True
+            for a, n in enumerate((nT, nH, nW)):
+                r = window[a] // 2
+                lo = 0 if n <= 2 * r + 1 else min(max(tu[a] - r, 0), n - 1 - 2 * r)
+                hi = n - 1 if n <= 2 * r + 1 else lo + 2 * r
+                ok = ok and lo <= tv[a] <= hi
+            assert keep[iu, iv] == ok
+    assert np.array_equal(fo.tile_mask(g, window + (fo.EDGE_SHIFT,)), keep)
+
+
 # ---- scales (Eq. 4) -----------------------------------------------------------------------
 def test_scale_equals_float32_division_for_every_bf16_amax():
     bits = (np.arange(1, 0x7F80, dtype=np.uint32) << np.uint32(16))     # all positive finite bf16
