@@ -40,6 +40,9 @@ struct AttnArgs {
     int chunk;             // work items per XCD
     int total;             // BH * M
     uint32_t partial_cls;  // bit c set iff boundary class c has padded tokens
+    // lane_mask[c][4b + r]: bit of lane (n, g) set iff the key that lane holds in accumulator slot
+    // (block b, element r), in-tile rank 16b + 4g + r, is a real token in a tile of class c
+    uint64_t lane_mask[8][32];
 };
 
 constexpr float kLog2eOverSqrtD = 0.12751743f;   // log2(e) / sqrt(128)
@@ -71,6 +74,14 @@ __device__ __forceinline__ bool work_item(const AttnArgs& a, int* bh, int* u) {
     *bh = wi / a.g.M;
     *u = wi - *bh * a.g.M;
     return true;
+}
+
+// x where the lane's bit of the wave-uniform mask is set, otherwise y: one v_cndmask with the mask
+// taken straight from scalar registers (no per-lane bit extraction).
+__device__ __forceinline__ float select_lanes(uint64_t lane_mask, float x, float y) {
+    float out;
+    asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(out) : "v"(y), "v"(x), "s"(lane_mask));
+    return out;
 }
 
 __device__ __forceinline__ int tile_class(const Geom& g, int t, int h, int w) {
@@ -294,12 +305,13 @@ void attn_fp8_kernel(AttnArgs a) {
     auto mask_scores = [&](int cls) {                      // padded keys of a boundary tile: -inf
         if ((a.partial_cls >> cls) & 1u) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const uint32_t bits = G.valid_mask[cls][b >> 1] >> (((b & 1) << 4) + 4 * g);
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
-            }
+                for (int r = 0; r < 4; ++r) {
+                    const uint64_t lm = a.lane_mask[cls][4 * b + r];   // uniform: one scalar load
+                    s[0][b][r] = select_lanes(lm, s[0][b][r], -INFINITY);
+                    s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
+                }
         }
     };
     auto rescale_acc = [&]() {                             // the row reference rarely moves
@@ -557,15 +569,16 @@ void attn_bf16_kernel(AttnArgs a) {
             asm volatile("" : "+v"(acc[qb][cb]));
         }
     };
-    auto mask_scores = [&](int cls) {
+    auto mask_scores = [&](int cls) {                      // padded keys of a boundary tile: -inf
         if ((a.partial_cls >> cls) & 1u) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const uint32_t bits = G.valid_mask[cls][b >> 1] >> (((b & 1) << 4) + 4 * g);
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
-            }
+                for (int r = 0; r < 4; ++r) {
+                    const uint64_t lm = a.lane_mask[cls][4 * b + r];   // uniform: one scalar load
+                    s[0][b][r] = select_lanes(lm, s[0][b][r], -INFINITY);
+                    s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
+                }
         }
     };
     auto rescale_acc = [&]() {
@@ -761,6 +774,16 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     for (int c = 0; c < 8; ++c)
         for (int w = 0; w < full_words; ++w)
             if (g.valid_mask[c][w] != 0xFFFFFFFFu) a.partial_cls |= 1u << c;
+    for (int c = 0; c < 8; ++c)
+        for (int i = 0; i < 32; ++i) {
+            uint64_t m = 0;
+            const int b = i >> 2, r = i & 3;
+            for (int lane = 0; lane < 64; ++lane) {
+                const int key = 16 * b + 4 * (lane >> 4) + r;
+                if (key < g.TS && ((g.valid_mask[c][key >> 5] >> (key & 31)) & 1u)) m |= 1ull << lane;
+            }
+            a.lane_mask[c][i] = m;
+        }
     const int grid = a.chunk * 8;
     if (prec == FPS_PREC_FP8) {
         const bool vch = vscale == FPS_VSCALE_CHANNEL;
