@@ -26,7 +26,11 @@
  * Padded slots of tiled inputs must be zero (fps_tile_order writes them so); padded keys never
  * contribute to any output and padded query rows are written as zero.
  *
- * Supported now: head_dim = 128 and TS in {32, 128}; anything else returns FPS_ERR_UNSUPPORTED.
+ * Supported now: head_dim = 128 and TS = 32 or any multiple of 128 up to 1024 (the granularity
+ * g(t) of Sec. 3.2 may therefore change the tile shape from one denoising regime to the next);
+ * anything else returns FPS_ERR_UNSUPPORTED.  The kernels work on blocks of 128 tokens (32 for
+ * TS = 32): a larger tile is TS/128 consecutive blocks that share one scale, and the packed
+ * operand layouts are per block.
  */
 #ifndef FPS_H
 #define FPS_H

@@ -13,6 +13,8 @@
 // range of the format).  The denominator accumulates the unrounded P.
 #include "fps_internal.h"
 
+#include <cstddef>
+#include <cstring>
 #include <type_traits>
 
 namespace fps {
@@ -32,18 +34,32 @@ struct AttnArgs {
     const float* sv;
     void* out;
     uint8_t* visited;
-    Geom g;
+    struct { int T, H, W, Tt, Th, Tw, nT, nH, nW, M, TS; } g;   // geometry without the mask tables
     int rt, rh, rw;        // window radii in tiles
     int edge_shift;        // 1: clamp the window centre into the grid instead of truncating
     int out_f32;
     int out_raster;        // output in raster order (real tokens only) instead of tile order
+    int KB;                // blocks per tile (g.KB)
     int chunk;             // work items per XCD
-    int total;             // BH * M
+    int total;             // BH * M * KB
     uint32_t partial_cls;  // bit c set iff boundary class c has padded tokens
+};
+
+// Second kernel parameter.  The kernels never name it: they read it through the kernel-argument
+// segment pointer (constant address space), so a wave-uniform index gives scalar loads and the
+// 3 KB of tables are never copied to private memory.
+struct MaskTables {
+    // valid[c][w]: bit (r & 31) of word (r >> 5) set iff in-tile rank r is a real token (class c)
+    uint32_t valid[8][kMaxTileWords];
     // lane_mask[c][4b + r]: bit of lane (n, g) set iff the key that lane holds in accumulator slot
-    // (block b, element r), in-tile rank 16b + 4g + r, is a real token in a tile of class c
+    // (block b, element r), rank 16b + 4g + r of a one-block tile, is a real token (class c)
     uint64_t lane_mask[8][32];
 };
+constexpr size_t kTablesOffset = (sizeof(AttnArgs) + 7) & ~size_t(7);   // kernarg offset of MaskTables
+
+// Every lambda of the kernels captures the accumulators by reference; left to the inliner's cost
+// model a large one stays a call, which forces everything it captures into private memory.
+#define FPS_INLINE __attribute__((always_inline))
 
 constexpr float kLog2eOverSqrtD = 0.12751743f;   // log2(e) / sqrt(128)
 constexpr float kLog2Of448 = 8.8073549f;          // log2(448)
@@ -67,13 +83,32 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 // Work item of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs by the hardware;
 // giving XCD x the contiguous range [x*chunk, (x+1)*chunk) of (bh, tile) items keeps the key
 // tiles of neighbouring query tiles of one head in that XCD's L2.
-__device__ __forceinline__ bool work_item(const AttnArgs& a, int* bh, int* u) {
+// A work item is one block of BS query rows: (bh, query tile u, block jq of the tile).
+__device__ __forceinline__ bool work_item(const AttnArgs& a, int KB, int* bh, int* u, int* jq) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int wi = xcd * a.chunk + slot;
     if (slot >= a.chunk || wi >= a.total) return false;
-    *bh = wi / a.g.M;
-    *u = wi - *bh * a.g.M;
+    const int tile_lin = wi / KB;
+    *jq = wi - tile_lin * KB;
+    *bh = tile_lin / a.g.M;
+    *u = tile_lin - *bh * a.g.M;
     return true;
+}
+
+// Tables inside the kernel-argument block, read through the constant address space with a
+// wave-uniform index so that they come in by scalar loads (indexing the by-value argument struct
+// directly can make the compiler spill it to private memory).
+__device__ __forceinline__ uint64_t arg_lane_mask(int cls, int i) {
+    typedef const __attribute__((address_space(4))) uint64_t* ptr_t;
+    const __attribute__((address_space(4))) char* base =
+        (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
+    return ((ptr_t)(base + kTablesOffset + offsetof(MaskTables, lane_mask)))[cls * 32 + i];
+}
+__device__ __forceinline__ uint32_t arg_valid_word(int cls, int w) {
+    typedef const __attribute__((address_space(4))) uint32_t* ptr_t;
+    const __attribute__((address_space(4))) char* base =
+        (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
+    return ((ptr_t)(base + kTablesOffset + offsetof(MaskTables, valid)))[cls * kMaxTileWords + w];
 }
 
 // x where the lane's bit of the wave-uniform mask is set, otherwise y: one v_cndmask with the mask
@@ -84,7 +119,8 @@ __device__ __forceinline__ float select_lanes(uint64_t lane_mask, float x, float
     return out;
 }
 
-__device__ __forceinline__ int tile_class(const Geom& g, int t, int h, int w) {
+template <typename G_>
+__device__ __forceinline__ int tile_class(const G_& g, int t, int h, int w) {
     return ((t == g.nT - 1) << 2) | ((h == g.nH - 1) << 1) | (w == g.nW - 1);
 }
 
@@ -94,10 +130,10 @@ __device__ __forceinline__ int tile_class(const Geom& g, int t, int h, int w) {
 // transposes its 16-row blocks through a private 16 KB LDS region and writes whole rows
 // (256 or 512 contiguous bytes).  The caller guarantees that no wave still reads the LDS buffers.
 template <int TS>
-__device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int ucls, int wave,
+__device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int jq, int ucls, int wave,
                                            int lane, const v4f (&acc)[2][8], const float (&inv)[2],
                                            uint8_t* wave_lds, const float* ch_scale = nullptr) {
-    const Geom& G = a.g;
+    const auto& G = a.g;
     const int g = lane >> 4, n = lane & 15;
     const int row_bytes = a.out_f32 ? 512 : 256;
     const int pitch = row_bytes + 16;                      // padding keeps the column writes off one bank
@@ -125,8 +161,8 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
         const int rows_per_pass = 64 / lanes_per_row;
         for (int r0 = 0; r0 < 16; r0 += rows_per_pass) {
             const int r = r0 + lane / lanes_per_row, chunk = lane % lanes_per_row;
-            const int rr = wave * 32 + qb * 16 + r;        // in-tile rank of the row
-            const bool valid = (G.valid_mask[ucls][rr >> 5] >> (rr & 31)) & 1u;
+            const int rr = jq * TS + wave * 32 + qb * 16 + r;   // in-tile rank of the row (TS: block size)
+            const bool valid = (arg_valid_word(ucls, rr >> 5) >> (rr & 31)) & 1u;
             uint4 val = *reinterpret_cast<const uint4*>(wave_lds + r * pitch + chunk * 16);
             size_t row;
             if (a.out_raster) {
@@ -134,7 +170,7 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
                 const int rw = rr % G.Tw, rh = (rr / G.Tw) % G.Th, rt = rr / (G.Tw * G.Th);
                 row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
             } else {
-                row = ((size_t)bh * G.M + u) * TS + rr;
+                row = ((size_t)bh * G.M + u) * G.TS + rr;
                 if (!valid) val = make_uint4(0, 0, 0, 0);
             }
             reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) + row * row_bytes)[chunk] = val;
@@ -144,13 +180,14 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
     }
 }
 
-// Walks the key-tile box of Eq. 2 in (t, h, w) order.
+// Walks the key-tile box of Eq. 2 in (t, h, w) order, block by block inside each tile.
 struct TileWalk {
     int t0, h0, w0, h1, w1;
     int vt, vh, vw;
-    int n;                                  // number of tiles in the box
-    __device__ __forceinline__ void init(const AttnArgs& a, int ut, int uh, int uw) {
-        const Geom& G = a.g;
+    int jk, kb;                             // block within the tile, blocks per tile
+    int n;                                  // number of key BLOCKS in the box
+    __device__ __forceinline__ void init(const AttnArgs& a, int KB, int ut, int uh, int uw) {
+        const auto& G = a.g;
         if (a.edge_shift) {                 // clamp the centre into [r, n-1-r]; an axis not longer than
             // the window has no such centre and is kept whole by the truncation below with u = n/2
             ut = G.nT > 2 * a.rt + 1 ? min(max(ut, a.rt), G.nT - 1 - a.rt) : G.nT / 2;
@@ -160,10 +197,13 @@ struct TileWalk {
         t0 = max(0, ut - a.rt); h0 = max(0, uh - a.rh); w0 = max(0, uw - a.rw);
         const int t1 = min(G.nT - 1, ut + a.rt);
         h1 = min(G.nH - 1, uh + a.rh); w1 = min(G.nW - 1, uw + a.rw);
-        n = (t1 - t0 + 1) * (h1 - h0 + 1) * (w1 - w0 + 1);
-        vt = t0; vh = h0; vw = w0;
+        kb = KB;
+        n = (t1 - t0 + 1) * (h1 - h0 + 1) * (w1 - w0 + 1) * kb;
+        vt = t0; vh = h0; vw = w0; jk = 0;
     }
     __device__ __forceinline__ void next() {
+        if (++jk < kb) return;
+        jk = 0;
         if (++vw > w1) { vw = w0; if (++vh > h1) { vh = h0; ++vt; } }
     }
 };
@@ -202,17 +242,18 @@ __device__ __forceinline__ void dma_chunk(const void* gsrc, uint32_t lane_off, u
 // K(i+2) and V(i) stream into LDS during iteration i; one barrier per iteration.
 // VCH: V carries one scale per channel (the paper's variant) instead of one per tile; the PV MFMA
 // then accumulates straight into O and the scales are applied once in the epilogue.
-template <int TS, bool VCH>
+template <int TS, bool VCH, bool MB>
 __global__ __launch_bounds__(TS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void attn_fp8_kernel(AttnArgs a) {
+void attn_fp8_kernel(AttnArgs a, MaskTables) {
     constexpr int NB = TS / 16;
     constexpr int NTHR = TS * 2;
     constexpr int CPT = (TS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
     constexpr int TILE_BYTES = TS * 128;
     __shared__ __attribute__((aligned(16))) uint8_t lds[4][TILE_BYTES];   // K even, K odd, V even, V odd
-    int bh, u;
-    if (!work_item(a, &bh, &u)) return;
-    const Geom& G = a.g;
+    const int KB = MB ? a.KB : 1;                          // blocks per tile; 1 is a compile-time fact
+    int bh, u, jq;
+    if (!work_item(a, KB, &bh, &u, &jq)) return;
+    const auto& G = a.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
     const size_t tile0 = (size_t)bh * G.M;
@@ -226,7 +267,8 @@ void attn_fp8_kernel(AttnArgs a) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wave * 32 + qb * 16 + n;
-        const uint4* p = reinterpret_cast<const uint4*>(a.q + ((tile0 + u) * TS + row) * 128 + 32 * g);
+        const uint4* p = reinterpret_cast<const uint4*>(
+            a.q + (((tile0 + u) * KB + jq) * TS + row) * 128 + 32 * g);
         qop[qb] = make_v8i(p[0], p[1]);
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -234,40 +276,40 @@ void attn_fp8_kernel(AttnArgs a) {
     const float sqc = load_uniform(a.sq, tile0 + u) * kLog2eOverSqrtD;
 
     TileWalk w0, w2;                                       // tile i, and the tile whose K is fetched (i+2)
-    w0.init(a, ut, uh, uw);
+    w0.init(a, KB, ut, uh, uw);
     w2 = w0;
     const int ntiles = w0.n;
-    auto tile_of = [&](const TileWalk& w) { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
+    auto tile_of = [&](const TileWalk& w) FPS_INLINE { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
 
     // chunk c (of CPT) of this thread's share of one operand tile, HBM -> lds[buf]
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the wave index, in a scalar register
-    auto stage_chunk = [&](int buf, const uint8_t* src, int c) {
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {
         dma_chunk(src + c * NTHR * 16, tid * 16,
                   lds_base + buf * TILE_BYTES + (c * NTHR + wave_s * 64) * 16);
     };
-    auto stage = [&](int buf, const uint8_t* src) {
+    auto stage = [&](int buf, const uint8_t* src) FPS_INLINE {
 #pragma unroll
         for (int c = 0; c < CPT; ++c) stage_chunk(buf, src, c);
     };
-    auto k_tile = [&](int v) { return a.k + (tile0 + v) * TILE_BYTES; };
-    auto v_tile = [&](int v) { return a.v + (tile0 + v) * TILE_BYTES; };
+    auto k_blk = [&](const TileWalk& w) FPS_INLINE { return a.k + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
+    auto v_blk = [&](const TileWalk& w) FPS_INLINE { return a.v + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
 
     v4f s[2][NB];
     v8i pb[2];                                             // P^T as packed E4M3, 4 keys per dword
     pb[0] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
     pb[1] = pb[0];
 
-    auto load_k = [&](const uint8_t* ldsK, int b) {
+    auto load_k = [&](const uint8_t* ldsK, int b) FPS_INLINE {
         const uint4* k4 = reinterpret_cast<const uint4*>(ldsK);
         return make_v8i(k4[(b * 2 + 0) * 64 + lane], k4[(b * 2 + 1) * 64 + lane]);
     };
-    auto qk_mfma = [&](const v8i& kop, int b) {            // S(b) = K(b) Q^T for both query blocks
+    auto qk_mfma = [&](const v8i& kop, int b) FPS_INLINE {            // S(b) = K(b) Q^T for both query blocks
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
             s[qb][b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
                 kop, qop[qb], v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
     };
-    auto load_v = [&](const uint8_t* ldsV, int cb) {
+    auto load_v = [&](const uint8_t* ldsV, int cb) FPS_INLINE {
         if constexpr (TS == 128) {
             const uint4* v4 = reinterpret_cast<const uint4*>(ldsV);
             return make_v8i(v4[(cb * 2 + 0) * 64 + lane], v4[(cb * 2 + 1) * 64 + lane]);
@@ -277,7 +319,7 @@ void attn_fp8_kernel(AttnArgs a) {
         }
     };
     // V^T(cb) P^T for both query blocks: raw into t (per-tile V scales) or accumulated into O (VCH)
-    auto pv_mfma = [&](const v8i& vop, v4f (&t)[2], int cb) {
+    auto pv_mfma = [&](const v8i& vop, v4f (&t)[2], int cb) FPS_INLINE {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const v4f c_in = VCH ? acc[qb][cb] : v4f{0.f, 0.f, 0.f, 0.f};
@@ -294,7 +336,7 @@ void attn_fp8_kernel(AttnArgs a) {
     };
     // O^T(cb) += s^V * t, pinned where it is written so that t does not stay live (the compiler
     // otherwise sinks all sixteen updates below the loop and spills)
-    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) {
+    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) FPS_INLINE {
         if (VCH) return;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -302,19 +344,30 @@ void attn_fp8_kernel(AttnArgs a) {
             asm volatile("" : "+v"(acc[qb][cb]));
         }
     };
-    auto mask_scores = [&](int cls) {                      // padded keys of a boundary tile: -inf
-        if ((a.partial_cls >> cls) & 1u) {
+    auto mask_scores = [&](int cls, int jk) FPS_INLINE {              // padded keys of a boundary tile: -inf
+        cls = __builtin_amdgcn_readfirstlane(cls);         // wave-uniform by construction
+        if (!((a.partial_cls >> cls) & 1u)) return;
+        if (!MB) {
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint64_t lm = a.lane_mask[cls][4 * b + r];   // uniform: one scalar load
+                    const uint64_t lm = arg_lane_mask(cls, 4 * b + r);   // uniform: one scalar load
                     s[0][b][r] = select_lanes(lm, s[0][b][r], -INFINITY);
                     s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
                 }
+        } else {                                           // block jk of a larger tile: test the bits
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const uint32_t bits = arg_valid_word(cls, __builtin_amdgcn_readfirstlane((jk * TS + 16 * b) >> 5))
+                                      >> (((b & 1) << 4) + 4 * g);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
+            }
         }
     };
-    auto rescale_acc = [&]() {                             // the row reference rarely moves
+    auto rescale_acc = [&]() FPS_INLINE {                             // the row reference rarely moves
         if (__any(alpha_prev[0] != 1.0f || alpha_prev[1] != 1.0f)) {
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb)
@@ -324,14 +377,14 @@ void attn_fp8_kernel(AttnArgs a) {
     };
 
     // prologue: K(0), K(1) staged; S(0) computed
-    stage(0, k_tile(tile_of(w2)));
+    stage(0, k_blk(w2));
     w2.next();
-    if (ntiles > 1) { stage(1, k_tile(tile_of(w2))); w2.next(); }
+    if (ntiles > 1) { stage(1, k_blk(w2)); w2.next(); }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < NB; ++b) qk_mfma(load_k(lds[0], b), b);
-    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
 
     float svv_prev = 0.f;
     float sc_next = sqc * load_uniform(a.sk, tile0 + tile_of(w0));   // scales of the coming tile
@@ -339,7 +392,7 @@ void attn_fp8_kernel(AttnArgs a) {
     // One iteration.  FIRST: there is no previous tile whose PV is owed.  LAST: there is no next
     // tile whose scores can be started.  Both are compile-time so that the MFMA / VALU interleave
     // of the steady state carries no branches.
-    auto iteration = [&](auto first_tag, auto last_tag, int it) {
+    auto iteration = [&](auto first_tag, auto last_tag, int it) FPS_INLINE {
         constexpr bool FIRST = decltype(first_tag)::value;
         constexpr bool LAST = decltype(last_tag)::value;
         const int par = it & 1;
@@ -348,13 +401,13 @@ void attn_fp8_kernel(AttnArgs a) {
         const int v = tile_of(w0);
         const float sc = sc_next;
         const float svv = sv_next;
-        if (a.visited && bh == 0 && tid == 0) a.visited[(size_t)u * G.M + v] = 1;
+        if (a.visited && bh == 0 && tid == 0 && jq == 0 && w0.jk == 0) a.visited[(size_t)u * G.M + v] = 1;
         __syncthreads();                 // every wave is past QK(i) and PV(i-2); staged tiles are visible
         // K(i+2) replaces K(i), V(i) goes to its own buffer; the copies are issued between the
         // MFMAs of phase 1 rather than in one burst (the load unit takes them slowly)
         const bool fetch_k = it + 2 < ntiles;
-        const uint8_t* ksrc = fetch_k ? k_tile(tile_of(w2)) : nullptr;
-        const uint8_t* vsrc = v_tile(v);
+        const uint8_t* ksrc = fetch_k ? k_blk(w2) : nullptr;
+        const uint8_t* vsrc = v_blk(w0);
         if (fetch_k) w2.next();
         w0.next();
         if (!LAST) {                     // scales of tile i+1, needed next iteration
@@ -435,7 +488,7 @@ void attn_fp8_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
-        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
         svv_prev = svv;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the staged tiles landed
     };
@@ -470,7 +523,7 @@ void attn_fp8_kernel(AttnArgs a) {
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
     __syncthreads();                                       // all waves are done with the staged tiles
-    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+    store_rows<TS>(a, bh, u, jq, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
                    &lds[0][0] + wave * kStoreRegionBytes, VCH ? a.sv + (size_t)bh * 128 : nullptr);
 }
 
@@ -484,18 +537,19 @@ void attn_fp8_kernel(AttnArgs a) {
 // ---------------------------------------------------------------------------------------------
 union Bf16x8 { uint4 u; v8bf v; v8h h; };
 
-template <int TS>
+template <int TS, bool MB>
 __global__ __launch_bounds__(TS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void attn_bf16_kernel(AttnArgs a) {
+void attn_bf16_kernel(AttnArgs a, MaskTables) {
     constexpr int NB = TS / 16;
     constexpr int NKK = TS / 32;
     constexpr int NTHR = TS * 2;
     constexpr int TILE_BYTES = TS * 256;
     constexpr int CPT = (TS * 16) / NTHR;                  // 16-byte chunks per thread per operand tile (8)
     __shared__ __attribute__((aligned(16))) uint8_t lds[2][TILE_BYTES];   // K, V
-    int bh, u;
-    if (!work_item(a, &bh, &u)) return;
-    const Geom& G = a.g;
+    const int KB = MB ? a.KB : 1;                          // blocks per tile; 1 is a compile-time fact
+    int bh, u, jq;
+    if (!work_item(a, KB, &bh, &u, &jq)) return;
+    const auto& G = a.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
     const size_t tile0 = (size_t)bh * G.M;
@@ -509,7 +563,7 @@ void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wave * 32 + qb * 16 + n;
-        const uint4* p = reinterpret_cast<const uint4*>(a.q + ((tile0 + u) * TS + row) * 256);
+        const uint4* p = reinterpret_cast<const uint4*>(a.q + (((tile0 + u) * KB + jq) * TS + row) * 256);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qop[qb][ks].u = p[ks * 4 + g];
 #pragma unroll
@@ -518,25 +572,25 @@ void attn_bf16_kernel(AttnArgs a) {
     const float sc = kLog2eOverSqrtD;
 
     TileWalk w0, w1;                                       // tile i and tile i+1
-    w0.init(a, ut, uh, uw);
+    w0.init(a, KB, ut, uh, uw);
     w1 = w0;
     w1.next();
     const int ntiles = w0.n;
-    auto tile_of = [&](const TileWalk& w) { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
+    auto tile_of = [&](const TileWalk& w) FPS_INLINE { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the wave index, in a scalar register
-    auto stage_chunk = [&](int buf, const uint8_t* src, int c) {
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {
         dma_chunk(src + c * NTHR * 16, tid * 16,
                   lds_base + buf * TILE_BYTES + (c * NTHR + wave_s * 64) * 16);
     };
-    auto k_tile = [&](int v) { return a.k + (tile0 + v) * TILE_BYTES; };
-    auto v_tile = [&](int v) { return a.v + (tile0 + v) * TILE_BYTES; };
+    auto k_blk = [&](const TileWalk& w) FPS_INLINE { return a.k + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
+    auto v_blk = [&](const TileWalk& w) FPS_INLINE { return a.v + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
     const uint4* ldsK4 = reinterpret_cast<const uint4*>(lds[0]);
     const uint4* ldsV4 = reinterpret_cast<const uint4*>(lds[1]);
 
     v4f s[2][NB];
     Bf16x8 pop[2][NKK];                                    // P^T in fp16, 8 keys per operand
 
-    auto qk_block = [&](int b) {                           // S(b) = K(b) Q^T, both query blocks
+    auto qk_block = [&](int b) FPS_INLINE {                           // S(b) = K(b) Q^T, both query blocks
         Bf16x8 kop[4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) kop[ks].u = ldsK4[(b * 4 + ks) * 64 + lane];
@@ -549,7 +603,7 @@ void attn_bf16_kernel(AttnArgs a) {
             s[qb][b] = r;
         }
     };
-    auto pv_block = [&](int cb, v4f (&t)[2]) {             // V^T(cb) P^T, raw, both query blocks
+    auto pv_block = [&](int cb, v4f (&t)[2]) FPS_INLINE {             // V^T(cb) P^T, raw, both query blocks
         Bf16x8 vop[NKK];
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) vop[kk].u = ldsV4[(kk * 8 + cb) * 64 + lane];
@@ -562,26 +616,37 @@ void attn_bf16_kernel(AttnArgs a) {
             t[qb] = r;
         }
     };
-    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) {
+    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) FPS_INLINE {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             acc[qb][cb] += t[qb] * svv;
             asm volatile("" : "+v"(acc[qb][cb]));
         }
     };
-    auto mask_scores = [&](int cls) {                      // padded keys of a boundary tile: -inf
-        if ((a.partial_cls >> cls) & 1u) {
+    auto mask_scores = [&](int cls, int jk) FPS_INLINE {              // padded keys of a boundary tile: -inf
+        cls = __builtin_amdgcn_readfirstlane(cls);         // wave-uniform by construction
+        if (!((a.partial_cls >> cls) & 1u)) return;
+        if (!MB) {
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint64_t lm = a.lane_mask[cls][4 * b + r];   // uniform: one scalar load
+                    const uint64_t lm = arg_lane_mask(cls, 4 * b + r);   // uniform: one scalar load
                     s[0][b][r] = select_lanes(lm, s[0][b][r], -INFINITY);
                     s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
                 }
+        } else {                                           // block jk of a larger tile: test the bits
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const uint32_t bits = arg_valid_word(cls, __builtin_amdgcn_readfirstlane((jk * TS + 16 * b) >> 5))
+                                      >> (((b & 1) << 4) + 4 * g);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
+            }
         }
     };
-    auto rescale_acc = [&]() {
+    auto rescale_acc = [&]() FPS_INLINE {
         if (__any(alpha_prev[0] != 1.0f || alpha_prev[1] != 1.0f)) {
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb)
@@ -592,22 +657,22 @@ void attn_bf16_kernel(AttnArgs a) {
 
     // prologue: K(0) staged, S(0) computed
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) stage_chunk(0, k_tile(tile_of(w0)), c);
+    for (int c = 0; c < CPT; ++c) stage_chunk(0, k_blk(w0), c);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < NB; ++b) qk_block(b);
-    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
 
     float svv_prev = 0.f;
-    auto iteration = [&](auto first_tag, auto last_tag) {
+    auto iteration = [&](auto first_tag, auto last_tag) FPS_INLINE {
         constexpr bool FIRST = decltype(first_tag)::value;
         constexpr bool LAST = decltype(last_tag)::value;
         const int v = tile_of(w0);
         const float svv = load_uniform(a.sv, tile0 + v);
-        if (a.visited && bh == 0 && tid == 0) a.visited[(size_t)u * G.M + v] = 1;
-        const uint8_t* ksrc = LAST ? nullptr : k_tile(tile_of(w1));
-        const uint8_t* vsrc = v_tile(v);
+        if (a.visited && bh == 0 && tid == 0 && jq == 0 && w0.jk == 0) a.visited[(size_t)u * G.M + v] = 1;
+        const uint8_t* ksrc = LAST ? nullptr : k_blk(w1);
+        const uint8_t* vsrc = v_blk(w0);
         __syncthreads();                 // every wave has finished QK(i): the K buffer is free; V(i-1) visible
 
         // ---- phase 1: row maxima of S(i)  |  delayed PV(i-1)  |  K(i+1) streams in ------------
@@ -680,7 +745,7 @@ void attn_bf16_kernel(AttnArgs a) {
         for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
         w0.next();
         w1.next();
-        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw));
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
         svv_prev = svv;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // V(i): this thread's share landed
     };
@@ -714,7 +779,7 @@ void attn_bf16_kernel(AttnArgs a) {
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;
     }
     __syncthreads();                                       // all waves are done with the staged tiles
-    store_rows<TS>(a, bh, u, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+    store_rows<TS>(a, bh, u, jq, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
                    &lds[0][0] + wave * kStoreRegionBytes);
 }
 
@@ -723,7 +788,7 @@ void attn_bf16_kernel(AttnArgs a) {
 template <int TS>
 __global__ __launch_bounds__(TS * 2) void scores_fp8_kernel(const uint8_t* __restrict__ q,
                                                             const uint8_t* __restrict__ k,
-                                                            float* __restrict__ out) {
+                                                            float* __restrict__ out, int out_pitch) {
     constexpr int NB = TS / 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const uint4* k4 = reinterpret_cast<const uint4*>(k);
@@ -739,18 +804,23 @@ __global__ __launch_bounds__(TS * 2) void scores_fp8_kernel(const uint8_t* __res
             const v4f s = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
                 kop, qop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) out[row * TS + 16 * b + 4 * g + r] = s[r];
+            for (int r = 0; r < 4; ++r) out[row * out_pitch + 16 * b + 4 * g + r] = s[r];
         }
     }
 }
 
 int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int v, float* out,
                       hipStream_t st) {
-    const size_t tile_bytes = (size_t)g.TS * 128;
-    const uint8_t* qp = (const uint8_t*)q + ((size_t)bh * g.M + u) * tile_bytes;
-    const uint8_t* kp = (const uint8_t*)k + ((size_t)bh * g.M + v) * tile_bytes;
-    if (g.TS == 128) scores_fp8_kernel<128><<<1, 256, 0, st>>>(qp, kp, out);
-    else             scores_fp8_kernel<32><<<1, 64, 0, st>>>(qp, kp, out);
+    // every (query block, key block) pair of the tile pair; out is [TS][TS], query-major
+    const size_t blk_bytes = (size_t)g.BS * 128;
+    for (int jq = 0; jq < g.KB; ++jq)
+        for (int jk = 0; jk < g.KB; ++jk) {
+            const uint8_t* qp = (const uint8_t*)q + (((size_t)bh * g.M + u) * g.KB + jq) * blk_bytes;
+            const uint8_t* kp = (const uint8_t*)k + (((size_t)bh * g.M + v) * g.KB + jk) * blk_bytes;
+            float* op = out + (size_t)jq * g.BS * g.TS + (size_t)jk * g.BS;
+            if (g.BS == 128) scores_fp8_kernel<128><<<1, 256, 0, st>>>(qp, kp, op, g.TS);
+            else             scores_fp8_kernel<32><<<1, 64, 0, st>>>(qp, kp, op, g.TS);
+        }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "debug scores launch");
 }
@@ -762,12 +832,16 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     a.q = (const uint8_t*)q; a.k = (const uint8_t*)k; a.v = (const uint8_t*)v;
     a.sq = sq; a.sk = sk; a.sv = sv;
     a.out = out; a.visited = visited;
-    a.g = g;
+    a.g.T = g.T; a.g.H = g.H; a.g.W = g.W; a.g.Tt = g.Tt; a.g.Th = g.Th; a.g.Tw = g.Tw;
+    a.g.nT = g.nT; a.g.nH = g.nH; a.g.nW = g.nW; a.g.M = g.M; a.g.TS = g.TS;
+    MaskTables t;
+    memcpy(t.valid, g.valid_mask, sizeof(t.valid));
     a.rt = win.wt / 2; a.rh = win.wh / 2; a.rw = win.ww / 2;
     a.edge_shift = win.edge == FPS_EDGE_SHIFT;
     a.out_f32 = out_f32;
     a.out_raster = out_raster;
-    a.total = g.BH * g.M;
+    a.KB = g.KB;
+    a.total = g.BH * g.M * g.KB;
     a.chunk = (a.total + 7) / 8;
     a.partial_cls = 0;
     const int full_words = g.TS / 32;
@@ -780,23 +854,33 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
             const int b = i >> 2, r = i & 3;
             for (int lane = 0; lane < 64; ++lane) {
                 const int key = 16 * b + 4 * (lane >> 4) + r;
-                if (key < g.TS && ((g.valid_mask[c][key >> 5] >> (key & 31)) & 1u)) m |= 1ull << lane;
+                if (key < g.BS && ((g.valid_mask[c][key >> 5] >> (key & 31)) & 1u)) m |= 1ull << lane;
             }
-            a.lane_mask[c][i] = m;
+            t.lane_mask[c][i] = m;
         }
     const int grid = a.chunk * 8;
+    const bool multi = g.KB > 1;                           // BS == 32 always has one block per tile
     if (prec == FPS_PREC_FP8) {
         const bool vch = vscale == FPS_VSCALE_CHANNEL;
-        if (g.TS == 128) {
-            if (vch) attn_fp8_kernel<128, true><<<grid, 256, 0, st>>>(a);
-            else     attn_fp8_kernel<128, false><<<grid, 256, 0, st>>>(a);
+        if (g.BS == 128) {
+            if (multi) {
+                if (vch) attn_fp8_kernel<128, true, true><<<grid, 256, 0, st>>>(a, t);
+                else     attn_fp8_kernel<128, false, true><<<grid, 256, 0, st>>>(a, t);
+            } else {
+                if (vch) attn_fp8_kernel<128, true, false><<<grid, 256, 0, st>>>(a, t);
+                else     attn_fp8_kernel<128, false, false><<<grid, 256, 0, st>>>(a, t);
+            }
         } else {
-            if (vch) attn_fp8_kernel<32, true><<<grid, 64, 0, st>>>(a);
-            else     attn_fp8_kernel<32, false><<<grid, 64, 0, st>>>(a);
+            if (vch) attn_fp8_kernel<32, true, false><<<grid, 64, 0, st>>>(a, t);
+            else     attn_fp8_kernel<32, false, false><<<grid, 64, 0, st>>>(a, t);
         }
     } else {
-        if (g.TS == 128) attn_bf16_kernel<128><<<grid, 256, 0, st>>>(a);
-        else             attn_bf16_kernel<32><<<grid, 64, 0, st>>>(a);
+        if (g.BS == 128) {
+            if (multi) attn_bf16_kernel<128, true><<<grid, 256, 0, st>>>(a, t);
+            else       attn_bf16_kernel<128, false><<<grid, 256, 0, st>>>(a, t);
+        } else {
+            attn_bf16_kernel<32, false><<<grid, 64, 0, st>>>(a, t);
+        }
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "attention launch");

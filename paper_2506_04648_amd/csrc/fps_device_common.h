@@ -1,0 +1,85 @@
+// Device helpers shared by the data-movement kernels of libfps (not part of the ABI).
+#pragma once
+#include "fps_internal.h"
+
+namespace fps {
+
+// The 16 uint4 (256 bytes) of one token's bf16 row.  `blk` is a block index over B*heads*M*KB,
+// `r` the token's position inside the block.  TILED input: blocks are contiguous.  RASTER input:
+// the token's (t,h,w) is recovered from its tile and in-tile rank; padded slots return nullptr.
+template <bool RASTER>
+__device__ __forceinline__ const uint4* token_row(const uint4* x, const Geom& g, long long blk, int r) {
+    if (!RASTER) return x + (blk * g.BS + r) * 16;
+    const long long tile_lin = blk / g.KB;
+    const int rank = (int)(blk % g.KB) * g.BS + r;
+    const int u = (int)(tile_lin % g.M);
+    const long long bh = tile_lin / g.M;
+    const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
+    const int rw = rank % g.Tw, rh = (rank / g.Tw) % g.Th, rt = rank / (g.Tw * g.Th);
+    const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
+    if (t >= g.T || h >= g.H || w >= g.W) return nullptr;
+    return x + ((((bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);
+}
+
+// max of the 15-bit magnitude patterns of 8 bf16 values (|x| of bf16 orders like that integer)
+__device__ __forceinline__ uint32_t amax_bits16(const uint4& v, uint32_t m) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+        m = lo > m ? lo : m;
+        m = hi > m ? hi : m;
+    }
+    return m;
+}
+
+// workgroup-wide max of m over 256 threads (red: 4 words of LDS); every thread gets the result
+__device__ __forceinline__ uint32_t block_max_256(uint32_t m, uint32_t* red) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)m, off);
+        m = o > m ? o : m;
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = red[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) m = red[i] > m ? red[i] : m;
+    return m;
+}
+
+__device__ __forceinline__ int pow2_exponent_for_fp16(float amax) {   // e with amax*2^-e in [2^14,2^15)
+    const uint32_t bits = __float_as_uint(amax);
+    int e = (int)((bits >> 23) & 0xFF) - 127 - 14;
+    return bits == 0 ? 0 : (e < -100 ? -100 : (e > 113 ? 113 : e));
+}
+
+// small in-place helpers (static: each translation unit that launches them has its own copy)
+static __global__ void clear_kernel(uint32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+static __global__ void amax_to_scale_kernel(float* p, int n) {       // amax -> amax/448 (1 for 0)
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { const float a = p[i]; p[i] = a == 0.0f ? 1.0f : a / 448.0f; }
+}
+static __global__ void amax_to_pow2_kernel(float* p, int n) {        // amax -> 2^e (see above)
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = __uint_as_float((uint32_t)(127 + pow2_exponent_for_fp16(p[i])) << 23);
+}
+// tile amax over the KB blocks of each tile: one workgroup per block, merged with an atomic max on
+// the float bit pattern (amax_bits must be cleared first)
+template <bool RASTER>
+__global__ __launch_bounds__(256) void block_amax_kernel(const uint4* __restrict__ x,
+                                                         uint32_t* __restrict__ amax_bits, Geom g) {
+    __shared__ uint32_t red[4];
+    uint32_t m = 0;
+    for (int c = threadIdx.x; c < g.BS * 16; c += 256) {
+        const uint4* row = token_row<RASTER>(x, g, blockIdx.x, c >> 4);
+        if (row) m = amax_bits16(row[c & 15], m);
+    }
+    m = block_max_256(m, red);
+    if (threadIdx.x == 0) atomicMax(&amax_bits[blockIdx.x / g.KB], m << 16);
+}
+
+}  // namespace fps

@@ -51,8 +51,9 @@ int check_shape(const fps_shape* s, Geom* g) {
         set_error("head_dim %d unsupported (only 128)", s->head_dim);
         return FPS_ERR_UNSUPPORTED;
     }
-    if (ts != 32 && ts != 128) {
-        set_error("tile of %lld tokens unsupported (only 32 or 128)", ts);
+    if (ts != 32 && !(ts % 128 == 0 && ts <= kMaxTileTokens)) {
+        set_error("tile of %lld tokens unsupported (32, or a multiple of 128 up to %d)", ts,
+                  kMaxTileTokens);
         return FPS_ERR_UNSUPPORTED;
     }
     if (!g) return FPS_OK;
@@ -61,11 +62,13 @@ int check_shape(const fps_shape* s, Geom* g) {
     g->Tt = s->Tt; g->Th = s->Th; g->Tw = s->Tw;
     g->nT = nT; g->nH = nH; g->nW = nW;
     g->M = (int)m; g->TS = (int)ts;
+    g->BS = ts == 32 ? 32 : 128;
+    g->KB = (int)ts / g->BS;
     const int lim_t[2] = {s->Tt, s->T - (nT - 1) * s->Tt};
     const int lim_h[2] = {s->Th, s->H - (nH - 1) * s->Th};
     const int lim_w[2] = {s->Tw, s->W - (nW - 1) * s->Tw};
     for (int c = 0; c < 8; ++c) {
-        for (int w = 0; w < 4; ++w) g->valid_mask[c][w] = 0;
+        for (int w = 0; w < kMaxTileWords; ++w) g->valid_mask[c][w] = 0;
         const int lt = lim_t[(c >> 2) & 1], lh = lim_h[(c >> 1) & 1], lw = lim_w[c & 1];
         for (int r = 0; r < (int)ts; ++r) {
             const int rw = r % s->Tw, rh = (r / s->Tw) % s->Th, rt = r / (s->Tw * s->Th);

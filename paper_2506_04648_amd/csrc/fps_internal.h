@@ -8,6 +8,8 @@
 namespace fps {
 
 constexpr int kHeadDim = 128;
+constexpr int kMaxTileTokens = 1024;                 // largest supported tile
+constexpr int kMaxTileWords = kMaxTileTokens / 32;
 
 // Everything the kernels derive from an fps_shape.
 struct Geom {
@@ -16,10 +18,13 @@ struct Geom {
     int Tt, Th, Tw;
     int nT, nH, nW;
     int M, TS;
+    // The kernels work on blocks of BS tokens (128, or 32 for 32-token tiles); a tile is KB = TS/BS
+    // consecutive blocks that share one scale.  Block index = tile index * KB + block in tile.
+    int BS, KB;
     // valid_mask[c][w]: bit (r & 31) of word (r >> 5) is set iff the token of in-tile rank r is a
     // real token in a tile of boundary class c = 4*(last tile along T) + 2*(last along H) +
     // (last along W).  A tile that is last along an axis keeps only T - (nT-1)*Tt (etc.) planes.
-    uint32_t valid_mask[8][4];
+    uint32_t valid_mask[8][kMaxTileWords];
 };
 
 void set_error(const char* fmt, ...);

@@ -15,7 +15,7 @@
 // key(g,s) is the key that slot s of lane group g holds after a 16x16 MFMA wrote S^T = K Q^T: the
 // accumulator of lane (n,g) for key block b has keys 16b + 4g + 0..3, so P^T can be fed back as
 // the second operand of the PV product without any cross-lane movement.
-#include "fps_internal.h"
+#include "fps_device_common.h"
 
 namespace fps {
 
@@ -61,21 +61,23 @@ __global__ void tile_unorder_kernel(const uint4* __restrict__ in, uint4* __restr
 }
 
 // ---- BF16 operand packing -----------------------------------------------------------------------
-// One workgroup of 256 threads per (bh, tile); the tile (TS*256 bytes) is staged in LDS.
+// One workgroup of 256 threads per block of BS tokens; the block (BS*256 bytes) is staged in LDS.
 // Q and K keep their bf16 values.  V is converted to fp16 so that the PV product can take P in
-// fp16 (11 significant bits instead of bf16's 8): each tile is first multiplied by 2^-e with
+// fp16 (11 significant bits instead of bf16's 8): each TILE is first multiplied by 2^-e with
 // amax * 2^-e in [2^14, 2^15), which keeps every bf16 value exact unless it is more than 2^28
 // times smaller than the tile's largest one, and vscale[tile] = 2^e undoes it in the kernel.
-template <int TS>
+// For tiles of several blocks the tile amax is computed beforehand (tile_amax != nullptr).
+template <int BS>
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict__ in,
                                                         uint4* __restrict__ out,
-                                                        float* __restrict__ vscale, int role) {
-    __shared__ uint16_t tile[TS * 128];
+                                                        float* __restrict__ vscale, int role, Geom g,
+                                                        const float* __restrict__ tile_amax) {
+    __shared__ uint16_t tile[BS * 128];
     __shared__ uint32_t red[4];
     const long long blk = blockIdx.x;
-    const uint4* src = in + blk * (TS * 16);
-    uint4* dst = out + blk * (TS * 16);
-    constexpr int kChunks = TS * 16;
+    const uint4* src = in + blk * (BS * 16);
+    uint4* dst = out + blk * (BS * 16);
+    constexpr int kChunks = BS * 16;
     if (role == FPS_ROLE_Q) {
         for (int c = threadIdx.x; c < kChunks; c += 256) dst[c] = src[c];
         return;
@@ -93,28 +95,19 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
     for (int c = threadIdx.x; c < kChunks; c += 256) {
         const uint4 v = src[c];
         t4[c] = v;
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
-            mb = lo > mb ? lo : mb;
-            mb = hi > mb ? hi : mb;
-        }
+        mb = amax_bits16(v, mb);
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)mb, off);
-        mb = o > mb ? o : mb;
+    float amax;
+    if (tile_amax) {
+        amax = tile_amax[blk / g.KB];
+        __syncthreads();
+    } else {
+        mb = block_max_256(mb, red);                       // also orders the LDS writes above
+        amax = __uint_as_float(mb << 16);
     }
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mb;
-    __syncthreads();
-    mb = red[0];
-#pragma unroll
-    for (int i = 1; i < 4; ++i) mb = red[i] > mb ? red[i] : mb;
-    int e = (int)(mb >> 7) - 127 - 14;                     // floor(log2(amax)) - 14
-    e = mb == 0 ? 0 : (e < -100 ? -100 : (e > 113 ? 113 : e));
+    const int e = pow2_exponent_for_fp16(amax);
     const float down = __uint_as_float((uint32_t)(127 - e) << 23);     // 2^-e
-    if (threadIdx.x == 0) vscale[blk] = __uint_as_float((uint32_t)(127 + e) << 23);
+    if (!tile_amax && threadIdx.x == 0) vscale[blk] = __uint_as_float((uint32_t)(127 + e) << 23);
     for (int c = threadIdx.x; c < kChunks; c += 256) {
         const int lane = c & 63, cb = (c >> 6) & 7, kk = c >> 9;
         const int gg = lane >> 4, n = lane & 15;
@@ -129,7 +122,7 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
 }
 
 // ---- debug unpack of E4M3 tensors ---------------------------------------------------------------
-template <int TS>
+template <int TS>                                         // TS here: tokens per BLOCK
 __global__ __launch_bounds__(256) void unpack_q8_kernel(const uint8_t* __restrict__ in,
                                                         uint8_t* __restrict__ out, int role) {
     const long long blk = blockIdx.x;
@@ -184,16 +177,23 @@ int launch_copy(const void* in, void* out, long long bytes, hipStream_t st) {
 }
 
 int launch_pack_bf16(const Geom& g, const void* x, int role, void* xp, float* vscale, hipStream_t st) {
-    const int blocks = g.BH * g.M;
-    if (g.TS == 128) pack_bf16_kernel<128><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role);
-    else             pack_bf16_kernel<32><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role);
+    const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M;
+    const float* tile_amax = nullptr;
+    if (role == FPS_ROLE_V && g.KB > 1) {                  // `vscale` holds the tile amax meanwhile
+        clear_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>((uint32_t*)vscale, ntiles);
+        block_amax_kernel<false><<<blocks, 256, 0, st>>>((const uint4*)x, (uint32_t*)vscale, g);
+        tile_amax = vscale;
+    }
+    if (g.BS == 128) pack_bf16_kernel<128><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role, g, tile_amax);
+    else             pack_bf16_kernel<32><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role, g, tile_amax);
+    if (tile_amax) amax_to_pow2_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>(vscale, ntiles);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "pack_bf16 launch");
 }
 
 int launch_unpack_q8(const Geom& g, const void* xq, int role, uint8_t* out, hipStream_t st) {
-    const int blocks = g.BH * g.M;
-    if (g.TS == 128) unpack_q8_kernel<128><<<blocks, 256, 0, st>>>((const uint8_t*)xq, out, role);
+    const int blocks = g.BH * g.M * g.KB;
+    if (g.BS == 128) unpack_q8_kernel<128><<<blocks, 256, 0, st>>>((const uint8_t*)xq, out, role);
     else             unpack_q8_kernel<32><<<blocks, 256, 0, st>>>((const uint8_t*)xq, out, role);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "unpack_q8 launch");

@@ -1,7 +1,7 @@
 // Per-tile amax -> scale -> E4M3 encode (Sec. 3.2, Eq. 4-5; Algorithm 1 step 2), writing the
 // packed operand layouts described in fps_layout.hip.  One workgroup of 256 threads per
 // (bh, tile); the pass is HBM-bound (2 bytes read, 1 byte written per element).
-#include "fps_internal.h"
+#include "fps_device_common.h"
 
 namespace fps {
 
@@ -67,77 +67,71 @@ __device__ __forceinline__ uint4 encode16(const uint4& lo, const uint4& hi, floa
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-__device__ __forceinline__ uint32_t amax_bits16(const uint4& v, uint32_t m) {
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+// V block in LDS (row-major codes [token][128]) -> key-contiguous packed layout in HBM
+template <int BS>
+__device__ __forceinline__ void write_v_block(const uint8_t* stage, uint4* dst, int tid) {
+    if (BS == 128) {
+        for (int c = tid; c < BS * 8; c += 256) {
+            const int lane = c & 63, h = (c >> 6) & 1, cb = c >> 7;
+            const int gg = lane >> 4, n = lane & 15;
+            union { uint4 v; uint8_t e[16]; } o;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
-        m = lo > m ? lo : m;
-        m = hi > m ? hi : m;
+            for (int jj = 0; jj < 16; ++jj)
+                o.e[jj] = stage[key_of_slot_q(gg, 16 * h + jj) * 128 + 16 * cb + n];
+            dst[c] = o.v;
+        }
+    } else {
+        uint2* dst8 = reinterpret_cast<uint2*>(dst);
+        for (int c = tid; c < BS * 16; c += 256) {
+            const int lane = c & 63, cb = c >> 6;
+            const int gg = lane >> 4, n = lane & 15;
+            union { uint2 v; uint8_t e[8]; } o;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+                o.e[jj] = stage[key_of_slot_q(gg, jj) * 128 + 16 * cb + n];
+            dst8[c] = o.v;
+        }
     }
-    return m;
 }
 
-// RASTER: x is the raster tensor [BH,T,H,W,128] and the tile's tokens are gathered from it (padded
-// slots read as zero), which fuses the tile ordering of Sec. 3.2 step (1) into this pass; otherwise
-// x is already tile-ordered.
-template <int TS, bool RASTER>
+// One workgroup of 256 threads per block of BS tokens.  A tile of one block (KB = 1) is handled in
+// a single pass: amax, scale, encode.  For larger tiles the tile amax comes from block_amax_kernel
+// (tile_amax != nullptr) and this kernel only encodes.
+// RASTER: x is the raster tensor [BH,T,H,W,128] and the block's tokens are gathered from it (padded
+// slots read as zero), which fuses the tile ordering of Sec. 3.2 step (1) into this pass.
+template <int BS, bool RASTER>
 __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __restrict__ x,
                                                              uint8_t* __restrict__ xq,
                                                              float* __restrict__ scales, int role,
-                                                             Geom g) {
-    constexpr int U = TS / 32;                      // 32-byte units (16 channels of one token) per thread
+                                                             Geom g, const float* __restrict__ tile_amax) {
+    constexpr int U = BS / 32;                      // 32-byte units (16 channels of one token) per thread
     __shared__ uint32_t red[4];
-    __shared__ __attribute__((aligned(16))) uint8_t stage[TS * 128];
+    __shared__ __attribute__((aligned(16))) uint8_t stage[BS * 128];
     const long long blk = blockIdx.x;
-    const uint4* src = x + blk * (TS * 16);
-    uint4* dst = reinterpret_cast<uint4*>(xq + blk * (TS * 128));
+    uint4* dst = reinterpret_cast<uint4*>(xq + blk * (BS * 128));
     const int tid = threadIdx.x;
-    int ut = 0, uh = 0, uw = 0;
-    long long bh = 0;
-    if (RASTER) {
-        const int u = (int)(blk % g.M);
-        bh = blk / g.M;
-        uw = u % g.nW; uh = (u / g.nW) % g.nH; ut = u / (g.nW * g.nH);
-    }
 
     uint4 lo[U], hi[U];
     uint32_t mb = 0;
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         const int unit = tid + 256 * i;              // token = unit >> 3, 16-channel group = unit & 7
-        if (RASTER) {
-            const int r = unit >> 3, c16 = unit & 7;
-            const int rw = r % g.Tw, rh = (r / g.Tw) % g.Th, rt = r / (g.Tw * g.Th);
-            const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
-            lo[i] = make_uint4(0, 0, 0, 0);
-            hi[i] = lo[i];
-            if (t < g.T && h < g.H && w < g.W) {
-                const uint4* row = x + ((((bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);
-                lo[i] = row[2 * c16];
-                hi[i] = row[2 * c16 + 1];
-            }
-        } else {
-            lo[i] = src[2 * unit];
-            hi[i] = src[2 * unit + 1];
-        }
+        const uint4* row = token_row<RASTER>(x, g, blk, unit >> 3);
+        lo[i] = make_uint4(0, 0, 0, 0);
+        hi[i] = lo[i];
+        if (row) { lo[i] = row[2 * (unit & 7)]; hi[i] = row[2 * (unit & 7) + 1]; }
         mb = amax_bits16(lo[i], mb);
         mb = amax_bits16(hi[i], mb);
     }
-    // |x| of bf16 values compares like the 15-bit integer pattern: integer max across the workgroup
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)mb, off);
-        mb = o > mb ? o : mb;
+    float amax;
+    if (tile_amax) {
+        amax = tile_amax[blk / g.KB];
+    } else {
+        mb = block_max_256(mb, red);
+        amax = __uint_as_float(mb << 16);
     }
-    if ((tid & 63) == 0) red[tid >> 6] = mb;
-    __syncthreads();
-    mb = red[0];
-#pragma unroll
-    for (int i = 1; i < 4; ++i) mb = red[i] > mb ? red[i] : mb;
-    const float amax = __uint_as_float(mb << 16);
-    const float s = (mb == 0) ? 1.0f : amax / 448.0f;    // Eq. 4 (correctly rounded division)
-    if (tid == 0) scales[blk] = s;
+    const float s = (amax == 0.0f) ? 1.0f : amax / 448.0f;   // Eq. 4 (correctly rounded division)
+    if (!tile_amax && tid == 0) scales[blk] = s;
 
 #pragma unroll
     for (int i = 0; i < U; ++i) {
@@ -155,53 +149,14 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __rest
     }
     if (role != FPS_ROLE_V) return;
     __syncthreads();
-    if (TS == 128) {
-        for (int c = tid; c < TS * 8; c += 256) {
-            const int lane = c & 63, h = (c >> 6) & 1, cb = c >> 7;
-            const int gg = lane >> 4, n = lane & 15;
-            union { uint4 v; uint8_t e[16]; } o;
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj)
-                o.e[jj] = stage[key_of_slot_q(gg, 16 * h + jj) * 128 + 16 * cb + n];
-            dst[c] = o.v;
-        }
-    } else {
-        uint2* dst8 = reinterpret_cast<uint2*>(dst);
-        for (int c = tid; c < TS * 16; c += 256) {
-            const int lane = c & 63, cb = c >> 6;
-            const int gg = lane >> 4, n = lane & 15;
-            union { uint2 v; uint8_t e[8]; } o;
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
-                o.e[jj] = stage[key_of_slot_q(gg, jj) * 128 + 16 * cb + n];
-            dst8[c] = o.v;
-        }
-    }
+    write_v_block<BS>(stage, dst, tid);
 }
 
 // ---- per-channel V (Sec. 3.2, Algorithm 1 step 3): s_c = max over ALL tokens of |V[:,c]| / 448 ----
-// Three stream-ordered kernels: clear the 128 per-head maxima; column maxima of every tile merged
-// with an atomic max on the bit pattern (|x| of a float orders like its unsigned pattern); encode
-// every tile with the per-channel scales; finally turn the stored maxima into scales in place.
-__global__ void clear_kernel(uint32_t* p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
-}
-
-template <bool RASTER>
-__device__ __forceinline__ const uint4* token_row(const uint4* x, const Geom& g, long long blk, int r,
-                                                  int TS) {
-    if (!RASTER) return x + (blk * TS + r) * 16;
-    const int u = (int)(blk % g.M);
-    const long long bh = blk / g.M;
-    const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
-    const int rw = r % g.Tw, rh = (r / g.Tw) % g.Th, rt = r / (g.Tw * g.Th);
-    const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
-    if (t >= g.T || h >= g.H || w >= g.W) return nullptr;
-    return x + ((((bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);
-}
-
-// one workgroup of 256 threads per (bh, tile): thread = (token group tid/16, 8-channel chunk tid%16)
+// Stream-ordered kernels: clear the 128 per-head maxima; column maxima of every block merged with
+// an atomic max on the bit pattern (|x| of a float orders like its unsigned pattern); encode every
+// block with the per-channel scales; finally turn the stored maxima into scales in place.
+// one workgroup of 256 threads per block: thread = (token group tid/16, 8-channel chunk tid%16)
 template <bool RASTER>
 __global__ __launch_bounds__(256) void channel_amax_kernel(const uint4* __restrict__ x,
                                                            uint32_t* __restrict__ amax_bits, Geom g) {
@@ -210,8 +165,8 @@ __global__ __launch_bounds__(256) void channel_amax_kernel(const uint4* __restri
     if (tid < 128) col[tid] = 0u;
     __syncthreads();
     uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int r = tid >> 4; r < g.TS; r += 16) {
-        const uint4* row = token_row<RASTER>(x, g, blockIdx.x, r, g.TS);
+    for (int r = tid >> 4; r < g.BS; r += 16) {
+        const uint4* row = token_row<RASTER>(x, g, blockIdx.x, r);
         if (!row) continue;
         const uint4 v = row[c8];
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -225,25 +180,27 @@ __global__ __launch_bounds__(256) void channel_amax_kernel(const uint4* __restri
 #pragma unroll
     for (int i = 0; i < 8; ++i) atomicMax(&col[c8 * 8 + i], m[i]);
     __syncthreads();
-    if (tid < 128) atomicMax(&amax_bits[(blockIdx.x / g.M) * 128 + tid], col[tid] << 16);
+    const long long bh = blockIdx.x / ((long long)g.M * g.KB);
+    if (tid < 128) atomicMax(&amax_bits[bh * 128 + tid], col[tid] << 16);
 }
 
-template <int TS, bool RASTER>
+template <int BS, bool RASTER>
 __global__ __launch_bounds__(256) void quantize_channels_kernel(const uint4* __restrict__ x,
                                                                 uint8_t* __restrict__ xq,
                                                                 const float* __restrict__ amax, Geom g) {
-    __shared__ __attribute__((aligned(16))) uint8_t stage[TS * 128];
+    __shared__ __attribute__((aligned(16))) uint8_t stage[BS * 128];
     __shared__ float sc[128];
     const int tid = threadIdx.x;
     const long long blk = blockIdx.x;
+    const long long bh = blk / ((long long)g.M * g.KB);
     if (tid < 128) {
-        const float a = amax[(blk / g.M) * 128 + tid];
+        const float a = amax[bh * 128 + tid];
         sc[tid] = a == 0.0f ? 1.0f : a / 448.0f;
     }
     __syncthreads();
-    for (int unit = tid; unit < TS * 8; unit += 256) {       // 16 channels of one token
+    for (int unit = tid; unit < BS * 8; unit += 256) {       // 16 channels of one token
         const int r = unit >> 3, c16 = unit & 7;
-        const uint4* row = token_row<RASTER>(x, g, blk, r, TS);
+        const uint4* row = token_row<RASTER>(x, g, blk, r);
         uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
         if (row) { lo = row[2 * c16]; hi = row[2 * c16 + 1]; }
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -261,49 +218,23 @@ __global__ __launch_bounds__(256) void quantize_channels_kernel(const uint4* __r
         reinterpret_cast<uint4*>(stage)[unit] = make_uint4(o[0], o[1], o[2], o[3]);
     }
     __syncthreads();
-    uint4* dst = reinterpret_cast<uint4*>(xq + blk * (TS * 128));
-    if (TS == 128) {
-        for (int c = tid; c < TS * 8; c += 256) {
-            const int lane = c & 63, h = (c >> 6) & 1, cb = c >> 7;
-            const int gg = lane >> 4, n = lane & 15;
-            union { uint4 v; uint8_t e[16]; } o;
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj)
-                o.e[jj] = stage[key_of_slot_q(gg, 16 * h + jj) * 128 + 16 * cb + n];
-            dst[c] = o.v;
-        }
-    } else {
-        uint2* dst8 = reinterpret_cast<uint2*>(dst);
-        for (int c = tid; c < TS * 16; c += 256) {
-            const int lane = c & 63, cb = c >> 6;
-            const int gg = lane >> 4, n = lane & 15;
-            union { uint2 v; uint8_t e[8]; } o;
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
-                o.e[jj] = stage[key_of_slot_q(gg, jj) * 128 + 16 * cb + n];
-            dst8[c] = o.v;
-        }
-    }
-}
-
-__global__ void amax_to_scale_kernel(float* p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) { const float a = p[i]; p[i] = a == 0.0f ? 1.0f : a / 448.0f; }
+    write_v_block<BS>(stage, reinterpret_cast<uint4*>(xq + blk * (BS * 128)), tid);
 }
 
 static int launch_quantize_channels(const Geom& g, const void* x, int raster, void* xq, float* scales,
                                     hipStream_t st) {
-    const int blocks = g.BH * g.M, n = g.BH * 128;
+    const int blocks = g.BH * g.M * g.KB, n = g.BH * 128;
     const uint4* xi = (const uint4*)x;
+    uint8_t* xo = (uint8_t*)xq;
     clear_kernel<<<(n + 255) / 256, 256, 0, st>>>((uint32_t*)scales, n);
     if (raster) channel_amax_kernel<true><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
     else        channel_amax_kernel<false><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
-    if (g.TS == 128) {
-        if (raster) quantize_channels_kernel<128, true><<<blocks, 256, 0, st>>>(xi, (uint8_t*)xq, scales, g);
-        else        quantize_channels_kernel<128, false><<<blocks, 256, 0, st>>>(xi, (uint8_t*)xq, scales, g);
+    if (g.BS == 128) {
+        if (raster) quantize_channels_kernel<128, true><<<blocks, 256, 0, st>>>(xi, xo, scales, g);
+        else        quantize_channels_kernel<128, false><<<blocks, 256, 0, st>>>(xi, xo, scales, g);
     } else {
-        if (raster) quantize_channels_kernel<32, true><<<blocks, 256, 0, st>>>(xi, (uint8_t*)xq, scales, g);
-        else        quantize_channels_kernel<32, false><<<blocks, 256, 0, st>>>(xi, (uint8_t*)xq, scales, g);
+        if (raster) quantize_channels_kernel<32, true><<<blocks, 256, 0, st>>>(xi, xo, scales, g);
+        else        quantize_channels_kernel<32, false><<<blocks, 256, 0, st>>>(xi, xo, scales, g);
     }
     amax_to_scale_kernel<<<(n + 255) / 256, 256, 0, st>>>(scales, n);
     hipError_t e = hipGetLastError();
@@ -313,16 +244,24 @@ static int launch_quantize_channels(const Geom& g, const void* x, int raster, vo
 int launch_quantize(const Geom& g, const void* x, int raster, int role, int vscale, void* xq,
                     float* scales, hipStream_t st) {
     if (vscale != FPS_VSCALE_TILE) return launch_quantize_channels(g, x, raster, xq, scales, st);
-    const int blocks = g.BH * g.M;
+    const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M;
     const uint4* xi = (const uint4*)x;
     uint8_t* xo = (uint8_t*)xq;
-    if (g.TS == 128) {
-        if (raster) quantize_tiles_kernel<128, true><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g);
-        else        quantize_tiles_kernel<128, false><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g);
-    } else {
-        if (raster) quantize_tiles_kernel<32, true><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g);
-        else        quantize_tiles_kernel<32, false><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g);
+    const float* tile_amax = nullptr;
+    if (g.KB > 1) {                     // tile amax over several blocks first; `scales` holds it meanwhile
+        clear_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>((uint32_t*)scales, ntiles);
+        if (raster) block_amax_kernel<true><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
+        else        block_amax_kernel<false><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
+        tile_amax = scales;
     }
+    if (g.BS == 128) {
+        if (raster) quantize_tiles_kernel<128, true><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
+        else        quantize_tiles_kernel<128, false><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
+    } else {
+        if (raster) quantize_tiles_kernel<32, true><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
+        else        quantize_tiles_kernel<32, false><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
+    }
+    if (g.KB > 1) amax_to_scale_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>(scales, ntiles);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "quantize_tiles launch");
 }

@@ -92,12 +92,15 @@ def gpu_raw_scores(run: GpuRun, head_slot, part):
     return raw[:, local]
 
 
-def fp8_tie_slack(run: GpuRun, head_slot, part):
+def fp8_tie_slack(run: GpuRun, head_slot, part, ref_rows):
     """Per output element: how far the oracle's result may legitimately move because the kernel
-    decides the E4M3 code of P from ITS score accumulators (exact products, hardware accumulation)
-    while the oracle decides it from the exact dot product.  The kernel's decision is re-enacted in
-    float32 from the raw scores it reports; elements whose code differs, elements within TAU of a
-    rounding boundary, and elements in the subnormal range of the format contribute."""
+    takes the softmax of ITS score accumulators (exact products, hardware accumulation, whose
+    error is bounded separately by score_error_ratio) while the oracle takes it of the exact dot
+    products.  The kernel's decisions are re-enacted in float32 from the raw scores it reports.
+    Two terms: (a) the E4M3 codes of P -- elements whose code differs, elements within TAU of a
+    rounding boundary, and elements in the subnormal range of the format; (b) the row sum l of
+    the unquantised weights, which scales the whole row (it matters only for rows whose scores
+    are large, where a relative score error of 2^-13 is an absolute error of 1e-2 in S')."""
     g = run.g
     (_, sq), (_, sk), _ = run.q8
     raw = gpu_raw_scores(run, head_slot, part)                          # float32
@@ -112,7 +115,10 @@ def fp8_tie_slack(run: GpuRun, head_slot, part):
     y_gpu = np.exp2(x.astype(np.float64))
     ph_gpu = e4m3.round_to_e4m3(y_gpu) / e4m3.FP8_MAX * np.exp2(m_gpu - part["m"])[:, None]
     d_elem = np.abs(ph_gpu - part["ph"]) + e4m3.rounding_slack(e4m3.FP8_MAX * part["p"], TAU) / e4m3.FP8_MAX
-    slack = (d_elem @ np.abs(part["v"])) / part["l"][:, None]
+    l_gpu = (y_gpu / e4m3.FP8_MAX).sum(axis=1) * np.exp2(m_gpu - part["m"])
+    l_min = np.minimum(l_gpu, part["l"])
+    slack = (d_elem @ np.abs(part["v"])) / l_min[:, None]
+    slack += np.abs(ref_rows) * (np.abs(l_gpu - part["l"]) / l_min)[:, None]
     slack[~part["rows_valid"]] = 0.0
     flips = int(np.count_nonzero(ph_gpu != part["ph"]))
     return slack, flips, ph_gpu.size
@@ -130,7 +136,7 @@ def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None, vs
     flips = elems = 0
     if prec == fps.PREC_FP8:
         for n, part in enumerate(parts):
-            sl, f, e = fp8_tie_slack(run, head_slot, part)
+            sl, f, e = fp8_tie_slack(run, head_slot, part, ref[n * g.TS:(n + 1) * g.TS])
             slack[n * g.TS:(n + 1) * g.TS] = sl
             flips += f
             elems += e

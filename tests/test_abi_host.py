@@ -76,6 +76,13 @@ def test_shape_validation():
     assert "head_dim" in fps.last_error()
     assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (1, 4, 4))) == 0      # 16-token tiles
     assert "unsupported" in fps.last_error()
+    # tiles of several 128-token blocks: any multiple of 128 up to 1024 tokens
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 8, 16))) == 4     # 256-token tiles
+    assert fps.num_tiles(fps.make_shape(2, (6, 16, 16), (6, 8, 8))) == 4      # 384
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (4, 16, 16))) == 1    # 1024
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 8, 12))) == 0     # 192: not a multiple
+    assert fps.num_tiles(fps.make_shape(2, (8, 16, 16), (8, 16, 16))) == 0    # 2048: too large
+    assert "unsupported" in fps.last_error()
     assert fps.num_tiles(fps.make_shape(0, (4, 16, 16), (2, 4, 4))) == 0
     assert L.fps_num_tiles(None) == 0
 

@@ -25,7 +25,8 @@ def tiny():
 
 # ---- layout and quantisation: bit exact -----------------------------------------------------
 @pytest.mark.parametrize("grid,tile", [((4, 16, 16), (2, 4, 4)), ((3, 5, 6), (2, 4, 4)),
-                                       ((2, 9, 20), (1, 8, 16)), ((3, 7, 9), (2, 4, 16))])
+                                       ((2, 9, 20), (1, 8, 16)), ((3, 7, 9), (2, 4, 16)),
+                                       ((3, 13, 20), (2, 8, 16)), ((7, 9, 10), (6, 8, 8))])
 def test_tile_order_roundtrip_bit_exact(grid, tile):
     import torch
     say("tile_order", grid, tile)
@@ -65,6 +66,18 @@ def test_quantize_ragged_128_token_tiles_bit_exact():
     say("quantize ragged 128")
     w = dataclasses.replace(synth.TINY, grid=(2, 13, 40), tile=(1, 8, 16), heads=2, n_outlier=3)
     _check_quantize(gu.GpuRun(w), range(2), "ragged128")
+
+
+@pytest.mark.parametrize("grid,tile", [((3, 13, 20), (2, 8, 16)),      # 256 tokens; last T tile half empty
+                                       ((7, 9, 10), (6, 8, 8)),         # 384 tokens, ragged on every axis
+                                       ((5, 16, 20), (4, 16, 16))])     # 1024 tokens, the largest tile
+def test_quantize_tiles_of_several_blocks_bit_exact(grid, tile):
+    """One scale per TILE although the kernels work on 128-token blocks (tile amax pre-pass)."""
+    say("quantize multi-block", grid, tile)
+    w = dataclasses.replace(synth.TINY, grid=grid, tile=tile, heads=2, n_outlier=3, config_id=15)
+    run = gu.GpuRun(w)
+    assert run.quantize()[0][1].shape[-1] == run.g.M
+    _check_quantize(run, range(2), f"multi-block {tile}")
 
 
 def test_quantize_special_values():
@@ -169,6 +182,9 @@ def test_attention_tiny_fp8_windows(tiny, window):
     ((1, 8, 16), (1, 8, 16), (1, 1, 1)),        # a single tile
     ((1, 3, 5), (1, 8, 16), (5, 5, 5)),         # a single, mostly padded tile
     ((5, 8, 16), (1, 8, 16), (2, 1, 1)),        # temporal-only window, even size
+    ((3, 13, 20), (2, 8, 16), (3, 3, 3)),       # 256-token tiles (2 blocks); one key block all padding
+    ((7, 9, 10), (6, 8, 8), (3, 1, 3)),         # 384-token tiles (3 blocks), ragged on every axis
+    ((5, 16, 20), (4, 16, 16), (3, 1, 1)),      # 1024-token tiles (8 blocks), the largest supported
 ])
 def test_attention_small_shapes(prec, grid, tile, window):
     say("attention small", prec, grid, tile, window)
@@ -184,7 +200,8 @@ def test_attention_small_shapes(prec, grid, tile, window):
 
 
 @pytest.mark.parametrize("grid,tile,window", [((4, 16, 16), (2, 4, 4), (1, 3, 3)),
-                                              ((2, 13, 40), (1, 8, 16), (3, 3, 3))])
+                                              ((2, 13, 40), (1, 8, 16), (3, 3, 3)),
+                                              ((3, 13, 20), (2, 8, 16), (3, 3, 3))])
 def test_per_channel_v_scales(grid, tile, window):
     """The paper's own V quantisation (Sec. 3.2): one scale per channel over all tokens."""
     import torch
@@ -273,7 +290,7 @@ def test_bf16_output_is_rounded_fp32_output(tiny):
 
 
 @pytest.mark.parametrize("grid,tile", [((4, 16, 16), (2, 4, 4)), ((3, 5, 6), (2, 4, 4)),
-                                       ((2, 13, 40), (1, 8, 16))])
+                                       ((2, 13, 40), (1, 8, 16)), ((3, 13, 20), (2, 8, 16))])
 def test_fused_raster_entry_points_match_the_unfused_path(grid, tile):
     """fps_quantize_raster == fps_tile_order + fps_quantize_tiles (bit for bit), and the raster
     output layout of fps_attn_fwd == fps_tile_unorder of the tiled output."""
