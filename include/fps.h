@@ -19,18 +19,20 @@
  *   - B and heads are interchangeable for the kernels: tensors are indexed by bh = b*heads + h.
  *
  * Token order.  A "raster" tensor is [B, heads, T, H, W, head_dim].  A "tiled" tensor is
- * [B, heads, M*TS, head_dim]: the grid is zero-padded up to multiples of the tile (Tt,Th,Tw), the
- * tile grid is (nT,nH,nW) = ceil((T,H,W)/(Tt,Th,Tw)), M = nT*nH*nW, TS = Tt*Th*Tw, token (t,h,w)
- * sits at position u*TS + r with u = ((t/Tt)*nH + h/Th)*nW + w/Tw and
+ * [B, heads, M*TSP, head_dim]: the grid is zero-padded up to multiples of the tile (Tt,Th,Tw), the
+ * tile grid is (nT,nH,nW) = ceil((T,H,W)/(Tt,Th,Tw)), M = nT*nH*nW, TS = Tt*Th*Tw, and token
+ * (t,h,w) sits at position u*TSP + r with u = ((t/Tt)*nH + h/Th)*nW + w/Tw and
  * r = ((t%Tt)*Th + h%Th)*Tw + w%Tw (Sec. 3.2 step (1): tokens of one 3D tile are contiguous).
- * Padded slots of tiled inputs must be zero (fps_tile_order writes them so); padded keys never
- * contribute to any output and padded query rows are written as zero.
+ * TSP = fps_tile_slots(shape) >= TS is the tile's slot count: the kernels work on blocks of 128
+ * tokens (32 when that wastes fewer slots, i.e. for TS <= 96), so a tile occupies TS rounded up
+ * to whole blocks and shares ONE scale over all of them; the packed operand layouts are per
+ * block.  Slots r >= TS, and slots of grid positions outside (T,H,W), are padding: they must be
+ * zero in tiled inputs (fps_tile_order writes them so); padded keys never contribute to any
+ * output and padded query rows are written as zero.
  *
- * Supported now: head_dim = 128 and TS = 32 or any multiple of 128 up to 1024 (the granularity
- * g(t) of Sec. 3.2 may therefore change the tile shape from one denoising regime to the next);
- * anything else returns FPS_ERR_UNSUPPORTED.  The kernels work on blocks of 128 tokens (32 for
- * TS = 32): a larger tile is TS/128 consecutive blocks that share one scale, and the packed
- * operand layouts are per block.
+ * Supported now: head_dim = 128 and any tile of 1 <= TS <= 32768 tokens, e.g. (1,8,16), (3,4,4),
+ * (6,8,8), (12,16,16), (24,32,32), so the granularity g(t) of Sec. 3.2 can change the tile shape
+ * from one denoising regime to the next; anything else returns FPS_ERR_UNSUPPORTED.
  */
 #ifndef FPS_H
 #define FPS_H
@@ -83,7 +85,9 @@ typedef enum {
  * whole axis (dense). */
 typedef struct { int wt, wh, ww; fps_edge edge; } fps_window;
 
-typedef struct { fps_precision prec; fps_window win; } fps_regime;
+/* One regime of the schedule: precision, window W(t), and the tile granularity g(t) (Eq. 6).
+ * Tt = Th = Tw = 0 means "whatever tile the shape of the call has". */
+typedef struct { fps_precision prec; fps_window win; int Tt, Th, Tw; } fps_regime;
 
 /* Denoising-step-aware schedule (Eq. 6): step t in 1..num_steps, thresholds t1 = alpha1*num_steps,
  * t2 = alpha2*num_steps evaluated in float; regime[0] if t <= t1, regime[1] if t1 < t <= t2,
@@ -105,7 +109,11 @@ int fps_schedule_select(const fps_step_cfg* cfg, fps_regime* out);
 /* M, the number of tiles per head, or 0 on an invalid shape. */
 size_t fps_num_tiles(const fps_shape* shape);
 
-/* Bytes of one packed tensor for the given precision (all B*heads): M*TS*head_dim bytes for FP8,
+/* TSP, the slots one tile occupies in tiled and packed tensors (TS rounded up to whole blocks),
+ * or 0 on an invalid shape. */
+size_t fps_tile_slots(const fps_shape* shape);
+
+/* Bytes of one packed tensor for the given precision (all B*heads): M*TSP*head_dim bytes for FP8,
  * twice that for BF16.  0 on an invalid shape. */
 size_t fps_packed_bytes(const fps_shape* shape, fps_precision prec);
 
@@ -117,12 +125,12 @@ int fps_tile_mask_host(const fps_shape* shape, const fps_window* win, uint8_t* m
 
 /* ---- device entry points ------------------------------------------------------------------ */
 
-/* Sec. 3.2 step (1).  raster bf16 [B,heads,T,H,W,128] (device) -> tiled bf16 [B,heads,M*TS,128]
+/* Sec. 3.2 step (1).  raster bf16 [B,heads,T,H,W,128] (device) -> tiled bf16 [B,heads,M*TSP,128]
  * (device), padded slots written as zero. */
 int fps_tile_order(const fps_shape* shape, const void* x_raster_bf16, void* x_tiled_bf16,
                    void* stream);
 
-/* Inverse of fps_tile_order for outputs: tiled [B,heads,M*TS,128] of dtype `dt` (device) ->
+/* Inverse of fps_tile_order for outputs: tiled [B,heads,M*TSP,128] of dtype `dt` (device) ->
  * raster [B,heads,T,H,W,128] of the same dtype (device). */
 int fps_tile_unorder(const fps_shape* shape, const void* o_tiled, fps_out_dtype dt, void* o_raster,
                      void* stream);
@@ -152,7 +160,7 @@ int fps_quantize_raster(const fps_shape* shape, const void* x_raster_bf16, fps_r
 int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
                         void* xp_out, float* vscale_out, void* stream);
 
-/* Debug: packed E4M3 tensor (device) -> plain row-major codes [B,heads,M*TS,128] (device). */
+/* Debug: packed E4M3 tensor (device) -> plain row-major codes [B,heads,M*TSP,128] (device). */
 int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,
                         uint8_t* codes_rowmajor, void* stream);
 
@@ -163,10 +171,18 @@ int fps_debug_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /* Debug: the raw score accumulators sum_c qcode_ic * kcode_jc (before the s^Q s^K / sqrt(d)
  * dequantisation of Eq. 3) of query tile u and key tile v of head bh, computed with the same
- * matrix instruction as fps_attn_fwd; `scores` is device memory of TS*TS floats, [query][key]
- * in in-tile rank order.  Used to measure the accumulation accuracy of the hardware. */
+ * matrix instruction as fps_attn_fwd; `scores` is device memory of TSP*TSP floats, [query][key]
+ * in in-tile slot order (entries of padding slots are zero products).  Used to measure the
+ * accumulation accuracy of the hardware; refused for TSP > 4096. */
 int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u, int v,
                         float* scores, void* stream);
+
+/* Debug: the same accumulators for ONE block pair, for tiles too large for the call above: query
+ * block jq of tile u against key block jk of tile v (blocks of BS = 32 or 128 slots, BS = TSP /
+ * blocks per tile; jq, jk in 0 .. TSP/BS - 1); `scores` is device memory of BS*BS floats,
+ * [query][key] in slot order within the blocks.  *bs_or_null receives BS (host memory). */
+int fps_debug_scores_block_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u,
+                              int jq, int v, int jk, float* scores, int* bs_or_null, void* stream);
 
 /* Eq. 2-3 and Sec. 3.2 "aggregation and dequantisation" (Algorithm 1 steps 4-5).
  *   q, k, v    packed tensors (device) made by fps_quantize_tiles (FP8) or fps_pack_tiles_bf16
@@ -174,8 +190,10 @@ int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, in
  *   sq, sk, sv fp32 scales (device) from fps_quantize_tiles; in BF16 mode sq and sk are ignored
  *              (may be NULL) and sv is the vscale_out of fps_pack_tiles_bf16.
  *   step       if non-NULL, (prec, win) are replaced by fps_schedule_select(step); the packed
- *              tensors must match the selected precision.
- *   out        of dtype out_dt (device): tiled [B,heads,M*TS,128] with padded query rows set to 0
+ *              tensors must match the selected precision, and if the selected regime names a
+ *              tile it must be the tile of `shape` (the inputs were quantised with it), else
+ *              FPS_ERR_INVALID_ARG.
+ *   out        of dtype out_dt (device): tiled [B,heads,M*TSP,128] with padded query rows set to 0
  *              (FPS_LAYOUT_TILED), or raster [B,heads,T,H,W,128] holding the real tokens only
  *              (FPS_LAYOUT_RASTER: the inverse tile ordering is fused into the epilogue).
  *   visited    NULL, or device memory of M*M bytes zeroed by the caller: the kernel sets

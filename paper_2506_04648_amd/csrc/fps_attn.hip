@@ -34,25 +34,22 @@ struct AttnArgs {
     const float* sv;
     void* out;
     uint8_t* visited;
-    struct { int T, H, W, Tt, Th, Tw, nT, nH, nW, M, TS; } g;   // geometry without the mask tables
+    Geom g;
     int rt, rh, rw;        // window radii in tiles
     int edge_shift;        // 1: clamp the window centre into the grid instead of truncating
     int out_f32;
     int out_raster;        // output in raster order (real tokens only) instead of tile order
-    int KB;                // blocks per tile (g.KB)
     int chunk;             // work items per XCD
     int total;             // BH * M * KB
-    uint32_t partial_cls;  // bit c set iff boundary class c has padded tokens
+    uint32_t partial_cls;  // bit c set iff a tile of boundary class c has padding slots
 };
 
-// Second kernel parameter.  The kernels never name it: they read it through the kernel-argument
-// segment pointer (constant address space), so a wave-uniform index gives scalar loads and the
-// 3 KB of tables are never copied to private memory.
+// Second kernel parameter, used by the one-block-per-tile kernels only.  They never name it: they
+// read it through the kernel-argument segment pointer (constant address space), so a wave-uniform
+// index gives scalar loads and the table is never copied to private memory.
 struct MaskTables {
-    // valid[c][w]: bit (r & 31) of word (r >> 5) set iff in-tile rank r is a real token (class c)
-    uint32_t valid[8][kMaxTileWords];
     // lane_mask[c][4b + r]: bit of lane (n, g) set iff the key that lane holds in accumulator slot
-    // (block b, element r), rank 16b + 4g + r of a one-block tile, is a real token (class c)
+    // (block b, element r), slot 16b + 4g + r of a one-block tile, is a real token (class c)
     uint64_t lane_mask[8][32];
 };
 constexpr size_t kTablesOffset = (sizeof(AttnArgs) + 7) & ~size_t(7);   // kernarg offset of MaskTables
@@ -63,6 +60,7 @@ constexpr size_t kTablesOffset = (sizeof(AttnArgs) + 7) & ~size_t(7);   // kerna
 
 constexpr float kLog2eOverSqrtD = 0.12751743f;   // log2(e) / sqrt(128)
 constexpr float kLog2Of448 = 8.8073549f;          // log2(448)
+constexpr float kFp16PScaleLog2 = 14.0f;          // BF16 mode holds 2^14 * P in fp16
 constexpr int kStoreRegionBytes = 16 * (512 + 16);  // per-wave LDS region of the output transpose
 
 // Scales are read-only for the whole launch and indexed uniformly: reading them through the constant
@@ -104,13 +102,6 @@ __device__ __forceinline__ uint64_t arg_lane_mask(int cls, int i) {
         (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
     return ((ptr_t)(base + kTablesOffset + offsetof(MaskTables, lane_mask)))[cls * 32 + i];
 }
-__device__ __forceinline__ uint32_t arg_valid_word(int cls, int w) {
-    typedef const __attribute__((address_space(4))) uint32_t* ptr_t;
-    const __attribute__((address_space(4))) char* base =
-        (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
-    return ((ptr_t)(base + kTablesOffset + offsetof(MaskTables, valid)))[cls * kMaxTileWords + w];
-}
-
 // x where the lane's bit of the wave-uniform mask is set, otherwise y: one v_cndmask with the mask
 // taken straight from scalar registers (no per-lane bit extraction).
 __device__ __forceinline__ float select_lanes(uint64_t lane_mask, float x, float y) {
@@ -161,8 +152,8 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
         const int rows_per_pass = 64 / lanes_per_row;
         for (int r0 = 0; r0 < 16; r0 += rows_per_pass) {
             const int r = r0 + lane / lanes_per_row, chunk = lane % lanes_per_row;
-            const int rr = jq * TS + wave * 32 + qb * 16 + r;   // in-tile rank of the row (TS: block size)
-            const bool valid = (arg_valid_word(ucls, rr >> 5) >> (rr & 31)) & 1u;
+            const int rr = jq * TS + wave * 32 + qb * 16 + r;   // the row's slot in its tile (TS: block size)
+            const bool valid = slot_is_token(G, ucls, rr);
             uint4 val = *reinterpret_cast<const uint4*>(wave_lds + r * pitch + chunk * 16);
             size_t row;
             if (a.out_raster) {
@@ -170,7 +161,7 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
                 const int rw = rr % G.Tw, rh = (rr / G.Tw) % G.Th, rt = rr / (G.Tw * G.Th);
                 row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
             } else {
-                row = ((size_t)bh * G.M + u) * G.TS + rr;
+                row = ((size_t)bh * G.M + u) * G.TSP + rr;
                 if (!valid) val = make_uint4(0, 0, 0, 0);
             }
             reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) + row * row_bytes)[chunk] = val;
@@ -180,14 +171,16 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
     }
 }
 
-// Walks the key-tile box of Eq. 2 in (t, h, w) order, block by block inside each tile.
+// Walks the key-tile box of Eq. 2 in (t, h, w) order, block by block inside each tile.  Blocks of
+// a last-along-T tile beyond kb_last hold padding only and are skipped.
 struct TileWalk {
     int t0, h0, w0, h1, w1;
     int vt, vh, vw;
-    int jk, kb;                             // block within the tile, blocks per tile
+    int jk, kb_cur;                         // block within the tile, blocks to visit in this tile
+    int kb_full, kb_last, last_t;
     int n;                                  // number of key BLOCKS in the box
-    __device__ __forceinline__ void init(const AttnArgs& a, int KB, int ut, int uh, int uw) {
-        const auto& G = a.g;
+    __device__ __forceinline__ void init(const AttnArgs& a, int KB, int KB_LAST, int ut, int uh, int uw) {
+        const Geom& G = a.g;
         if (a.edge_shift) {                 // clamp the centre into [r, n-1-r]; an axis not longer than
             // the window has no such centre and is kept whole by the truncation below with u = n/2
             ut = G.nT > 2 * a.rt + 1 ? min(max(ut, a.rt), G.nT - 1 - a.rt) : G.nT / 2;
@@ -197,16 +190,42 @@ struct TileWalk {
         t0 = max(0, ut - a.rt); h0 = max(0, uh - a.rh); w0 = max(0, uw - a.rw);
         const int t1 = min(G.nT - 1, ut + a.rt);
         h1 = min(G.nH - 1, uh + a.rh); w1 = min(G.nW - 1, uw + a.rw);
-        kb = KB;
-        n = (t1 - t0 + 1) * (h1 - h0 + 1) * (w1 - w0 + 1) * kb;
+        kb_full = KB; kb_last = KB_LAST; last_t = G.nT - 1;
+        const int has_last = t1 == last_t;
+        n = (h1 - h0 + 1) * (w1 - w0 + 1) * ((t1 - t0 + 1 - has_last) * KB + has_last * KB_LAST);
         vt = t0; vh = h0; vw = w0; jk = 0;
+        kb_cur = vt == last_t ? kb_last : kb_full;
     }
     __device__ __forceinline__ void next() {
-        if (++jk < kb) return;
+        if (++jk < kb_cur) return;
         jk = 0;
-        if (++vw > w1) { vw = w0; if (++vh > h1) { vh = h0; ++vt; } }
+        if (++vw > w1) {
+            vw = w0;
+            if (++vh > h1) { vh = h0; ++vt; kb_cur = vt == last_t ? kb_last : kb_full; }
+        }
     }
 };
+
+// A query block that holds padding only: its rows of a tile-ordered output are zero, a raster
+// output has no such rows.  TS: block size, NTHR: threads of the workgroup.
+template <int TS, int NTHR>
+__device__ __forceinline__ void zero_block_rows(const AttnArgs& a, int bh, int u, int jq) {
+    if (a.out_raster) return;
+    const int row_bytes = a.out_f32 ? 512 : 256;
+    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) +
+                                          (((size_t)bh * a.g.M + u) * a.g.TSP + (size_t)jq * TS) * row_bytes);
+    for (int i = threadIdx.x; i < TS * (row_bytes / 16); i += NTHR) dst[i] = make_uint4(0, 0, 0, 0);
+}
+
+// Validity of the TS slots of block jk of a tile of class cls as wave-wide ballots: bit i of
+// word h says whether slot 64h + i of the block is a real token.  Evaluated arithmetically, so
+// that tiles of any size need no table.
+template <int TS>
+__device__ __forceinline__ void block_ballots(const Geom& G, int cls, int jk, int lane,
+                                              uint64_t (&bm)[(TS + 63) / 64]) {
+#pragma unroll
+    for (int h = 0; h < (TS + 63) / 64; ++h) bm[h] = __ballot(slot_is_token(G, cls, jk * TS + 64 * h + lane));
+}
 
 __device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
     return v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
@@ -250,12 +269,17 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     constexpr int CPT = (TS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
     constexpr int TILE_BYTES = TS * 128;
     __shared__ __attribute__((aligned(16))) uint8_t lds[4][TILE_BYTES];   // K even, K odd, V even, V odd
-    const int KB = MB ? a.KB : 1;                          // blocks per tile; 1 is a compile-time fact
+    const Geom& G = a.g;
+    const int KB = MB ? G.KB : 1;                          // blocks per tile; 1 is a compile-time fact
+    const int KB_LAST = MB ? G.kb_last : 1;                // ... of a last-along-T tile, without padding-only blocks
     int bh, u, jq;
     if (!work_item(a, KB, &bh, &u, &jq)) return;
-    const auto& G = a.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
+    if (MB && jq >= (ut == G.nT - 1 ? KB_LAST : KB)) {      // a query block of padding only
+        zero_block_rows<TS, TS * 2>(a, bh, u, jq);
+        return;
+    }
     const size_t tile0 = (size_t)bh * G.M;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(&lds[0][0]);   // LDS byte address of buffer 0
 
@@ -276,7 +300,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     const float sqc = load_uniform(a.sq, tile0 + u) * kLog2eOverSqrtD;
 
     TileWalk w0, w2;                                       // tile i, and the tile whose K is fetched (i+2)
-    w0.init(a, KB, ut, uh, uw);
+    w0.init(a, KB, KB_LAST, ut, uh, uw);
     w2 = w0;
     const int ntiles = w0.n;
     auto tile_of = [&](const TileWalk& w) FPS_INLINE { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
@@ -356,11 +380,16 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
                     s[0][b][r] = select_lanes(lm, s[0][b][r], -INFINITY);
                     s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
                 }
-        } else {                                           // block jk of a larger tile: test the bits
+        } else {                                           // block jk of a larger tile
+            uint64_t bm[(TS + 63) / 64];
+            block_ballots<TS>(G, cls, jk, lane, bm);
+            bool all = true;
+#pragma unroll
+            for (int h = 0; h < (TS + 63) / 64; ++h) all = all && (bm[h] | (TS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
+            if (all) return;                               // most blocks of a boundary tile are whole
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const uint32_t bits = arg_valid_word(cls, __builtin_amdgcn_readfirstlane((jk * TS + 16 * b) >> 5))
-                                      >> (((b & 1) << 4) + 4 * g);
+                const uint32_t bits = ((uint32_t)(bm[(16 * b) >> 6] >> ((16 * b) & 63)) & 0xFFFFu) >> (4 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
@@ -546,12 +575,17 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     constexpr int TILE_BYTES = TS * 256;
     constexpr int CPT = (TS * 16) / NTHR;                  // 16-byte chunks per thread per operand tile (8)
     __shared__ __attribute__((aligned(16))) uint8_t lds[2][TILE_BYTES];   // K, V
-    const int KB = MB ? a.KB : 1;                          // blocks per tile; 1 is a compile-time fact
+    const Geom& G = a.g;
+    const int KB = MB ? G.KB : 1;                          // blocks per tile; 1 is a compile-time fact
+    const int KB_LAST = MB ? G.kb_last : 1;                // ... of a last-along-T tile, without padding-only blocks
     int bh, u, jq;
     if (!work_item(a, KB, &bh, &u, &jq)) return;
-    const auto& G = a.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
+    if (MB && jq >= (ut == G.nT - 1 ? KB_LAST : KB)) {      // a query block of padding only
+        zero_block_rows<TS, TS * 2>(a, bh, u, jq);
+        return;
+    }
     const size_t tile0 = (size_t)bh * G.M;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(&lds[0][0]);
 
@@ -572,7 +606,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     const float sc = kLog2eOverSqrtD;
 
     TileWalk w0, w1;                                       // tile i and tile i+1
-    w0.init(a, KB, ut, uh, uw);
+    w0.init(a, KB, KB_LAST, ut, uh, uw);
     w1 = w0;
     w1.next();
     const int ntiles = w0.n;
@@ -635,11 +669,16 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
                     s[0][b][r] = select_lanes(lm, s[0][b][r], -INFINITY);
                     s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
                 }
-        } else {                                           // block jk of a larger tile: test the bits
+        } else {                                           // block jk of a larger tile
+            uint64_t bm[(TS + 63) / 64];
+            block_ballots<TS>(G, cls, jk, lane, bm);
+            bool all = true;
+#pragma unroll
+            for (int h = 0; h < (TS + 63) / 64; ++h) all = all && (bm[h] | (TS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
+            if (all) return;                               // most blocks of a boundary tile are whole
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const uint32_t bits = arg_valid_word(cls, __builtin_amdgcn_readfirstlane((jk * TS + 16 * b) >> 5))
-                                      >> (((b & 1) << 4) + 4 * g);
+                const uint32_t bits = ((uint32_t)(bm[(16 * b) >> 6] >> ((16 * b) & 63)) & 0xFFFFu) >> (4 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     if (!((bits >> r) & 1u)) { s[0][b][r] = -INFINITY; s[1][b][r] = -INFINITY; }
@@ -709,7 +748,10 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
             const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(t * sc));
             alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
             m_run[qb] = m_new;
-            cm[qb] = -m_new;
+            // 2^14 * 2^(S' - m): the factor rides in the exponent and cancels against the row sum,
+            // which is taken of the same scaled values; it keeps weights down to 2^-28 in fp16's
+            // normal range (a dense row over thousands of keys has many weights below 2^-14)
+            cm[qb] = kFp16PScaleLog2 - m_new;
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // K(i+1): this thread's share landed
         __syncthreads();                 // every wave has finished PV(i-1): the V buffer is free; K(i+1) visible
@@ -786,10 +828,14 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
 // Debug: raw E4M3 score accumulators sum_c q_ic * k_jc of one tile pair, produced by the same MFMA
 // instruction and operand layouts as attn_fp8_kernel; out[i*TS + j], query-major.
 template <int TS>
-__global__ __launch_bounds__(TS * 2) void scores_fp8_kernel(const uint8_t* __restrict__ q,
-                                                            const uint8_t* __restrict__ k,
-                                                            float* __restrict__ out, int out_pitch) {
+__global__ __launch_bounds__(TS * 2) void scores_fp8_kernel(const uint8_t* __restrict__ q_tile,
+                                                            const uint8_t* __restrict__ k_tile,
+                                                            float* __restrict__ out_tile, int out_pitch) {
     constexpr int NB = TS / 16;
+    // workgroup (x, y) = (key block, query block) of the tile pair
+    const uint8_t* q = q_tile + (size_t)blockIdx.y * TS * 128;
+    const uint8_t* k = k_tile + (size_t)blockIdx.x * TS * 128;
+    float* out = out_tile + (size_t)blockIdx.y * TS * out_pitch + (size_t)blockIdx.x * TS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const uint4* k4 = reinterpret_cast<const uint4*>(k);
 #pragma unroll
@@ -804,25 +850,33 @@ __global__ __launch_bounds__(TS * 2) void scores_fp8_kernel(const uint8_t* __res
             const v4f s = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
                 kop, qop, v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) out[row * out_pitch + 16 * b + 4 * g + r] = s[r];
+            for (int r = 0; r < 4; ++r) out[(size_t)row * out_pitch + 16 * b + 4 * g + r] = s[r];
         }
     }
 }
 
 int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int v, float* out,
                       hipStream_t st) {
-    // every (query block, key block) pair of the tile pair; out is [TS][TS], query-major
-    const size_t blk_bytes = (size_t)g.BS * 128;
-    for (int jq = 0; jq < g.KB; ++jq)
-        for (int jk = 0; jk < g.KB; ++jk) {
-            const uint8_t* qp = (const uint8_t*)q + (((size_t)bh * g.M + u) * g.KB + jq) * blk_bytes;
-            const uint8_t* kp = (const uint8_t*)k + (((size_t)bh * g.M + v) * g.KB + jk) * blk_bytes;
-            float* op = out + (size_t)jq * g.BS * g.TS + (size_t)jk * g.BS;
-            if (g.BS == 128) scores_fp8_kernel<128><<<1, 256, 0, st>>>(qp, kp, op, g.TS);
-            else             scores_fp8_kernel<32><<<1, 64, 0, st>>>(qp, kp, op, g.TS);
-        }
+    // every (query block, key block) pair of the tile pair; out is [TSP][TSP], query-major
+    const size_t tile_bytes = (size_t)g.TSP * 128;
+    const uint8_t* qp = (const uint8_t*)q + ((size_t)bh * g.M + u) * tile_bytes;
+    const uint8_t* kp = (const uint8_t*)k + ((size_t)bh * g.M + v) * tile_bytes;
+    const dim3 grid(g.KB, g.KB);
+    if (g.BS == 128) scores_fp8_kernel<128><<<grid, 256, 0, st>>>(qp, kp, out, g.TSP);
+    else             scores_fp8_kernel<32><<<grid, 64, 0, st>>>(qp, kp, out, g.TSP);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "debug scores launch");
+}
+
+int launch_scores_block_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int jq, int v,
+                            int jk, float* out, hipStream_t st) {
+    const size_t blk_bytes = (size_t)g.BS * 128;
+    const uint8_t* qp = (const uint8_t*)q + (((size_t)bh * g.M + u) * g.KB + jq) * blk_bytes;
+    const uint8_t* kp = (const uint8_t*)k + (((size_t)bh * g.M + v) * g.KB + jk) * blk_bytes;
+    if (g.BS == 128) scores_fp8_kernel<128><<<dim3(1, 1), 256, 0, st>>>(qp, kp, out, g.BS);
+    else             scores_fp8_kernel<32><<<dim3(1, 1), 64, 0, st>>>(qp, kp, out, g.BS);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "debug block scores launch");
 }
 
 int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, const void* k,
@@ -832,56 +886,58 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     a.q = (const uint8_t*)q; a.k = (const uint8_t*)k; a.v = (const uint8_t*)v;
     a.sq = sq; a.sk = sk; a.sv = sv;
     a.out = out; a.visited = visited;
-    a.g.T = g.T; a.g.H = g.H; a.g.W = g.W; a.g.Tt = g.Tt; a.g.Th = g.Th; a.g.Tw = g.Tw;
-    a.g.nT = g.nT; a.g.nH = g.nH; a.g.nW = g.nW; a.g.M = g.M; a.g.TS = g.TS;
-    MaskTables t;
-    memcpy(t.valid, g.valid_mask, sizeof(t.valid));
+    a.g = g;
     a.rt = win.wt / 2; a.rh = win.wh / 2; a.rw = win.ww / 2;
     a.edge_shift = win.edge == FPS_EDGE_SHIFT;
     a.out_f32 = out_f32;
     a.out_raster = out_raster;
-    a.KB = g.KB;
     a.total = g.BH * g.M * g.KB;
     a.chunk = (a.total + 7) / 8;
     a.partial_cls = 0;
-    const int full_words = g.TS / 32;
     for (int c = 0; c < 8; ++c)
-        for (int w = 0; w < full_words; ++w)
-            if (g.valid_mask[c][w] != 0xFFFFFFFFu) a.partial_cls |= 1u << c;
-    for (int c = 0; c < 8; ++c)
-        for (int i = 0; i < 32; ++i) {
-            uint64_t m = 0;
-            const int b = i >> 2, r = i & 3;
-            for (int lane = 0; lane < 64; ++lane) {
-                const int key = 16 * b + 4 * (lane >> 4) + r;
-                if (key < g.BS && ((g.valid_mask[c][key >> 5] >> (key & 31)) & 1u)) m |= 1ull << lane;
+        if (g.TS != g.TSP || ((c & 4) && g.lastT < g.Tt) || ((c & 2) && g.lastH < g.Th) ||
+            ((c & 1) && g.lastW < g.Tw))
+            a.partial_cls |= 1u << c;
+    MaskTables t;
+    memset(&t, 0, sizeof(t));
+    if (g.KB == 1) {
+        for (int c = 0; c < 8; ++c) {
+            bool ok[128];
+            for (int r = 0; r < 128; ++r) ok[r] = r < g.BS && slot_is_token(g, c, r);
+            for (int i = 0; i < 32; ++i) {
+                uint64_t m = 0;
+                const int b = i >> 2, r = i & 3;
+                for (int lane = 0; lane < 64; ++lane)
+                    if (ok[16 * b + 4 * (lane >> 4) + r]) m |= 1ull << lane;
+                t.lane_mask[c][i] = m;
             }
-            t.lane_mask[c][i] = m;
-        }
-    const int grid = a.chunk * 8;
-    const bool multi = g.KB > 1;                           // BS == 32 always has one block per tile
-    if (prec == FPS_PREC_FP8) {
-        const bool vch = vscale == FPS_VSCALE_CHANNEL;
-        if (g.BS == 128) {
-            if (multi) {
-                if (vch) attn_fp8_kernel<128, true, true><<<grid, 256, 0, st>>>(a, t);
-                else     attn_fp8_kernel<128, false, true><<<grid, 256, 0, st>>>(a, t);
-            } else {
-                if (vch) attn_fp8_kernel<128, true, false><<<grid, 256, 0, st>>>(a, t);
-                else     attn_fp8_kernel<128, false, false><<<grid, 256, 0, st>>>(a, t);
-            }
-        } else {
-            if (vch) attn_fp8_kernel<32, true, false><<<grid, 64, 0, st>>>(a, t);
-            else     attn_fp8_kernel<32, false, false><<<grid, 64, 0, st>>>(a, t);
-        }
-    } else {
-        if (g.BS == 128) {
-            if (multi) attn_bf16_kernel<128, true><<<grid, 256, 0, st>>>(a, t);
-            else       attn_bf16_kernel<128, false><<<grid, 256, 0, st>>>(a, t);
-        } else {
-            attn_bf16_kernel<32, false><<<grid, 64, 0, st>>>(a, t);
         }
     }
+    const int grid = a.chunk * 8;
+    const bool multi = g.KB > 1;
+    const bool vch = vscale == FPS_VSCALE_CHANNEL;
+#define FPS_LAUNCH_FP8(BS_, THREADS_)                                                              \
+    do {                                                                                           \
+        if (multi) {                                                                               \
+            if (vch) attn_fp8_kernel<BS_, true, true><<<grid, THREADS_, 0, st>>>(a, t);            \
+            else     attn_fp8_kernel<BS_, false, true><<<grid, THREADS_, 0, st>>>(a, t);           \
+        } else {                                                                                   \
+            if (vch) attn_fp8_kernel<BS_, true, false><<<grid, THREADS_, 0, st>>>(a, t);           \
+            else     attn_fp8_kernel<BS_, false, false><<<grid, THREADS_, 0, st>>>(a, t);          \
+        }                                                                                          \
+    } while (0)
+#define FPS_LAUNCH_BF16(BS_, THREADS_)                                                             \
+    do {                                                                                           \
+        if (multi) attn_bf16_kernel<BS_, true><<<grid, THREADS_, 0, st>>>(a, t);                   \
+        else       attn_bf16_kernel<BS_, false><<<grid, THREADS_, 0, st>>>(a, t);                  \
+    } while (0)
+    if (prec == FPS_PREC_FP8) {
+        if (g.BS == 128) FPS_LAUNCH_FP8(128, 256); else FPS_LAUNCH_FP8(32, 64);
+    } else {
+        if (g.BS == 128) FPS_LAUNCH_BF16(128, 256); else FPS_LAUNCH_BF16(32, 64);
+    }
+#undef FPS_LAUNCH_FP8
+#undef FPS_LAUNCH_BF16
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "attention launch");
 }

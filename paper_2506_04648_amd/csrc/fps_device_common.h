@@ -4,21 +4,41 @@
 
 namespace fps {
 
-// The 16 uint4 (256 bytes) of one token's bf16 row.  `blk` is a block index over B*heads*M*KB,
-// `r` the token's position inside the block.  TILED input: blocks are contiguous.  RASTER input:
-// the token's (t,h,w) is recovered from its tile and in-tile rank; padded slots return nullptr.
+// Where a block of BS slots sits: its head, the grid origin of its tile and its first slot.
+// Computed once per workgroup (the divisions are by run-time values).
+struct BlockOrigin {
+    long long bh;
+    int t0, h0, w0;      // grid coordinates of the tile's first token
+    int slot0;           // first in-tile slot of the block
+};
+__device__ __forceinline__ BlockOrigin block_origin(const Geom& g, int blk) {
+    BlockOrigin o;
+    const int tile_lin = blk / g.KB;                     // 32-bit: the block count fits a grid dimension
+    o.slot0 = (blk - tile_lin * g.KB) * g.BS;
+    const int bh = tile_lin / g.M;
+    const int u = tile_lin - bh * g.M;
+    const int ut = u / (g.nW * g.nH), rem = u - ut * (g.nW * g.nH);
+    const int uh = rem / g.nW, uw = rem - uh * g.nW;
+    o.bh = bh;
+    o.t0 = ut * g.Tt; o.h0 = uh * g.Th; o.w0 = uw * g.Tw;
+    return o;
+}
+
+// The 16 uint4 (256 bytes) of the bf16 row of the token in slot r of block `blk`.  TILED input:
+// blocks are contiguous.  RASTER input: the token's (t,h,w) is recovered from the tile origin and
+// the in-tile slot; padding slots return nullptr.
 template <bool RASTER>
-__device__ __forceinline__ const uint4* token_row(const uint4* x, const Geom& g, long long blk, int r) {
-    if (!RASTER) return x + (blk * g.BS + r) * 16;
-    const long long tile_lin = blk / g.KB;
-    const int rank = (int)(blk % g.KB) * g.BS + r;
-    const int u = (int)(tile_lin % g.M);
-    const long long bh = tile_lin / g.M;
-    const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
-    const int rw = rank % g.Tw, rh = (rank / g.Tw) % g.Th, rt = rank / (g.Tw * g.Th);
-    const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
+__device__ __forceinline__ const uint4* token_row(const uint4* x, const Geom& g, const BlockOrigin& o,
+                                                  int blk, int r) {
+    if (!RASTER) return x + ((long long)blk * g.BS + r) * 16;
+    const int slot = o.slot0 + r;
+    if (slot >= g.TS) return nullptr;                    // slots past the tile's tokens are padding
+    const int plane = g.Th * g.Tw;
+    const int rt = slot / plane, rem = slot - rt * plane;
+    const int rh = rem / g.Tw, rw = rem - rh * g.Tw;
+    const int t = o.t0 + rt, h = o.h0 + rh, w = o.w0 + rw;
     if (t >= g.T || h >= g.H || w >= g.W) return nullptr;
-    return x + ((((bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);
+    return x + ((((o.bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);
 }
 
 // max of the 15-bit magnitude patterns of 8 bf16 values (|x| of bf16 orders like that integer)
@@ -74,8 +94,9 @@ __global__ __launch_bounds__(256) void block_amax_kernel(const uint4* __restrict
                                                          uint32_t* __restrict__ amax_bits, Geom g) {
     __shared__ uint32_t red[4];
     uint32_t m = 0;
+    const BlockOrigin org = block_origin(g, blockIdx.x);
     for (int c = threadIdx.x; c < g.BS * 16; c += 256) {
-        const uint4* row = token_row<RASTER>(x, g, blockIdx.x, c >> 4);
+        const uint4* row = token_row<RASTER>(x, g, org, blockIdx.x, c >> 4);
         if (row) m = amax_bits16(row[c & 15], m);
     }
     m = block_max_256(m, red);

@@ -43,18 +43,20 @@ int check_shape(const fps_shape* s, Geom* g) {
     const int nT = (s->T + s->Tt - 1) / s->Tt, nH = (s->H + s->Th - 1) / s->Th,
               nW = (s->W + s->Tw - 1) / s->Tw;
     const long long m = (long long)nT * nH * nW;
-    if (bh > (1 << 20) || m > (1 << 20) || ts > (1 << 20) || bh * m > (1LL << 28)) {
-        set_error("shape too large (B*heads*M must stay below 2^28)");
-        return FPS_ERR_INVALID_ARG;
-    }
     if (s->head_dim != kHeadDim) {
         set_error("head_dim %d unsupported (only 128)", s->head_dim);
         return FPS_ERR_UNSUPPORTED;
     }
-    if (ts != 32 && !(ts % 128 == 0 && ts <= kMaxTileTokens)) {
-        set_error("tile of %lld tokens unsupported (32, or a multiple of 128 up to %d)", ts,
-                  kMaxTileTokens);
+    if (ts > kMaxTileTokens) {
+        set_error("tile of %lld tokens unsupported (at most %d)", ts, kMaxTileTokens);
         return FPS_ERR_UNSUPPORTED;
+    }
+    // 32-token blocks when they waste fewer slots than 128-token blocks (TS <= 96)
+    const int bs = (ts <= 128 && (ts + 31) / 32 * 32 < 128) ? 32 : 128;
+    const int kb = (int)((ts + bs - 1) / bs);
+    if (bh > (1 << 20) || m > (1 << 20) || bh * m * kb >= (1LL << 30)) {
+        set_error("shape too large (B*heads*M*blocks-per-tile must stay below 2^30)");
+        return FPS_ERR_INVALID_ARG;
     }
     if (!g) return FPS_OK;
     g->BH = (int)bh;
@@ -62,19 +64,11 @@ int check_shape(const fps_shape* s, Geom* g) {
     g->Tt = s->Tt; g->Th = s->Th; g->Tw = s->Tw;
     g->nT = nT; g->nH = nH; g->nW = nW;
     g->M = (int)m; g->TS = (int)ts;
-    g->BS = ts == 32 ? 32 : 128;
-    g->KB = (int)ts / g->BS;
-    const int lim_t[2] = {s->Tt, s->T - (nT - 1) * s->Tt};
-    const int lim_h[2] = {s->Th, s->H - (nH - 1) * s->Th};
-    const int lim_w[2] = {s->Tw, s->W - (nW - 1) * s->Tw};
-    for (int c = 0; c < 8; ++c) {
-        for (int w = 0; w < kMaxTileWords; ++w) g->valid_mask[c][w] = 0;
-        const int lt = lim_t[(c >> 2) & 1], lh = lim_h[(c >> 1) & 1], lw = lim_w[c & 1];
-        for (int r = 0; r < (int)ts; ++r) {
-            const int rw = r % s->Tw, rh = (r / s->Tw) % s->Th, rt = r / (s->Tw * s->Th);
-            if (rt < lt && rh < lh && rw < lw) g->valid_mask[c][r >> 5] |= 1u << (r & 31);
-        }
-    }
+    g->BS = bs; g->KB = kb; g->TSP = kb * bs;
+    g->lastT = s->T - (nT - 1) * s->Tt;
+    g->lastH = s->H - (nH - 1) * s->Th;
+    g->lastW = s->W - (nW - 1) * s->Tw;
+    g->kb_last = (g->lastT * s->Th * s->Tw + bs - 1) / bs;
     return FPS_OK;
 }
 
@@ -119,6 +113,12 @@ int fps_schedule_select(const fps_step_cfg* cfg, fps_regime* out) {
     for (int i = 0; i < 3; ++i) {
         FPS_TRY(check_enum(cfg->regime[i].prec, FPS_PREC_FP8, "regime.prec"));
         FPS_TRY(check_window(&cfg->regime[i].win));
+        const fps_regime& r = cfg->regime[i];
+        const bool none = r.Tt == 0 && r.Th == 0 && r.Tw == 0;
+        if (!none && (r.Tt <= 0 || r.Th <= 0 || r.Tw <= 0)) {
+            set_error("regime %d: tile (%d,%d,%d) must be all zero or all positive", i, r.Tt, r.Th, r.Tw);
+            return FPS_ERR_INVALID_ARG;
+        }
     }
     const float t1 = cfg->alpha1 * (float)cfg->num_steps;
     const float t2 = cfg->alpha2 * (float)cfg->num_steps;
@@ -133,11 +133,17 @@ size_t fps_num_tiles(const fps_shape* shape) {
     return (size_t)g.M;
 }
 
+size_t fps_tile_slots(const fps_shape* shape) {
+    Geom g;
+    if (check_shape(shape, &g) != FPS_OK) return 0;
+    return (size_t)g.TSP;
+}
+
 size_t fps_packed_bytes(const fps_shape* shape, fps_precision prec) {
     Geom g;
     if (check_shape(shape, &g) != FPS_OK) return 0;
     if (check_enum(prec, FPS_PREC_FP8, "prec") != FPS_OK) return 0;
-    const size_t n = (size_t)g.BH * g.M * g.TS * kHeadDim;
+    const size_t n = (size_t)g.BH * g.M * g.TSP * kHeadDim;
     return prec == FPS_PREC_FP8 ? n : 2 * n;
 }
 
@@ -266,7 +272,27 @@ int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, in
         set_error("bh/u/v out of range");
         return FPS_ERR_INVALID_ARG;
     }
+    if (g.TSP > kMaxScoreSlots) {
+        set_error("score debug call refused for tiles of more than %d slots", kMaxScoreSlots);
+        return FPS_ERR_UNSUPPORTED;
+    }
     return launch_scores_fp8(g, q, k, bh, u, v, scores, (hipStream_t)stream);
+}
+
+int fps_debug_scores_block_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u,
+                              int jq, int v, int jk, float* scores, int* bs_or_null, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_ptr(q, "q"));
+    FPS_TRY(check_ptr(k, "k"));
+    FPS_TRY(check_ptr(scores, "scores"));
+    if (bh < 0 || bh >= g.BH || u < 0 || u >= g.M || v < 0 || v >= g.M || jq < 0 || jq >= g.KB ||
+        jk < 0 || jk >= g.KB) {
+        set_error("bh/u/v/jq/jk out of range");
+        return FPS_ERR_INVALID_ARG;
+    }
+    if (bs_or_null) *bs_or_null = g.BS;
+    return launch_scores_block_fp8(g, q, k, bh, u, jq, v, jk, scores, (hipStream_t)stream);
 }
 
 int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision prec,
@@ -278,11 +304,17 @@ int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision pr
     fps_regime sel;
     if (step) {
         FPS_TRY(fps_schedule_select(step, &sel));
+        if (sel.Tt != 0 && (sel.Tt != shape->Tt || sel.Th != shape->Th || sel.Tw != shape->Tw)) {
+            set_error("step %d selects tile (%d,%d,%d) but the shape of the call has (%d,%d,%d)",
+                      step->step, sel.Tt, sel.Th, sel.Tw, shape->Tt, shape->Th, shape->Tw);
+            return FPS_ERR_INVALID_ARG;
+        }
     } else {
         FPS_TRY(check_window(win));
         FPS_TRY(check_enum(prec, FPS_PREC_FP8, "prec"));
         sel.prec = prec;
         sel.win = *win;
+        sel.Tt = sel.Th = sel.Tw = 0;
     }
     FPS_TRY(check_enum(vscale, FPS_VSCALE_CHANNEL, "vscale"));
     FPS_TRY(check_enum(out_dt, FPS_OUT_F32, "out_dt"));

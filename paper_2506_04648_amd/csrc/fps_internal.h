@@ -8,8 +8,8 @@
 namespace fps {
 
 constexpr int kHeadDim = 128;
-constexpr int kMaxTileTokens = 1024;                 // largest supported tile
-constexpr int kMaxTileWords = kMaxTileTokens / 32;
+constexpr int kMaxTileTokens = 32768;                // largest supported tile
+constexpr int kMaxScoreSlots = 4096;                 // largest tile the score debug call accepts
 
 // Everything the kernels derive from an fps_shape.
 struct Geom {
@@ -18,14 +18,27 @@ struct Geom {
     int Tt, Th, Tw;
     int nT, nH, nW;
     int M, TS;
-    // The kernels work on blocks of BS tokens (128, or 32 for 32-token tiles); a tile is KB = TS/BS
-    // consecutive blocks that share one scale.  Block index = tile index * KB + block in tile.
-    int BS, KB;
-    // valid_mask[c][w]: bit (r & 31) of word (r >> 5) is set iff the token of in-tile rank r is a
-    // real token in a tile of boundary class c = 4*(last tile along T) + 2*(last along H) +
-    // (last along W).  A tile that is last along an axis keeps only T - (nT-1)*Tt (etc.) planes.
-    uint32_t valid_mask[8][kMaxTileWords];
+    // The kernels work on blocks of BS tokens (128 or 32); a tile occupies KB = ceil(TS/BS)
+    // consecutive blocks, TSP = KB*BS slots, and has ONE scale.  Block index = tile * KB + block
+    // in tile.  Slot r of a tile holds the token of in-tile rank r if r < TS, else padding.
+    int BS, KB, TSP;
+    // Real planes / rows / columns of the LAST tile along each axis (all others are full).  A
+    // tile's boundary class is c = 4*(last along T) + 2*(last along H) + (last along W).
+    int lastT, lastH, lastW;
+    // Blocks of a last-along-T tile that hold at least one real token: its slots from
+    // lastT*Th*Tw on are all padding, so those blocks are never computed.
+    int kb_last;
 };
+
+// slot r of a tile of boundary class c holds a real token
+__host__ __device__ inline bool slot_is_token(const Geom& g, int c, int r) {
+    if (r >= g.TS) return false;
+    const int plane = g.Th * g.Tw;
+    const int rt = r / plane, rem = r - rt * plane;
+    const int rh = rem / g.Tw, rw = rem - rh * g.Tw;
+    return rt < ((c & 4) ? g.lastT : g.Tt) && rh < ((c & 2) ? g.lastH : g.Th) &&
+           rw < ((c & 1) ? g.lastW : g.Tw);
+}
 
 void set_error(const char* fmt, ...);
 int check_shape(const fps_shape* s, Geom* g);          // validates, fills g
@@ -46,5 +59,7 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
 int launch_copy(const void* in, void* out, long long bytes, hipStream_t st);
 int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int v, float* out,
                       hipStream_t st);
+int launch_scores_block_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int jq, int v,
+                            int jk, float* out, hipStream_t st);
 
 }  // namespace fps

@@ -27,16 +27,16 @@ __global__ void tile_order_kernel(const uint4* __restrict__ in, uint4* __restric
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_chunks) return;
     const int c16 = (int)(i & 15);
-    const long long pos = i >> 4;                       // bh * (M*TS) + u*TS + r
-    const int r = (int)(pos % g.TS);
-    const long long bu = pos / g.TS;
+    const long long pos = i >> 4;                       // bh * (M*TSP) + u*TSP + r
+    const int r = (int)(pos % g.TSP);
+    const long long bu = pos / g.TSP;
     const int u = (int)(bu % g.M);
     const long long bh = bu / g.M;
     const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
     const int rw = r % g.Tw, rh = (r / g.Tw) % g.Th, rt = r / (g.Tw * g.Th);
     const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (t < g.T && h < g.H && w < g.W) {
+    if (r < g.TS && t < g.T && h < g.H && w < g.W) {
         const long long src = (((bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16 + c16;
         val = in[src];
     }
@@ -56,7 +56,7 @@ __global__ void tile_unorder_kernel(const uint4* __restrict__ in, uint4* __restr
     const long long bh = tok / g.T;
     const int u = ((t / g.Tt) * g.nH + h / g.Th) * g.nW + w / g.Tw;
     const int r = ((t % g.Tt) * g.Th + h % g.Th) * g.Tw + w % g.Tw;
-    const long long src = ((bh * g.M + u) * (long long)g.TS + r) * chunks_per_row + c;
+    const long long src = ((bh * g.M + u) * (long long)g.TSP + r) * chunks_per_row + c;
     out[i] = in[src];
 }
 
@@ -155,7 +155,7 @@ __global__ void copy_kernel(const uint4* __restrict__ in, uint4* __restrict__ ou
 static inline int grid_for(long long n, int block) { return (int)((n + block - 1) / block); }
 
 int launch_tile_order(const Geom& g, const void* in, void* out, hipStream_t st) {
-    const long long n = (long long)g.BH * g.M * g.TS * 16;
+    const long long n = (long long)g.BH * g.M * g.TSP * 16;
     tile_order_kernel<<<grid_for(n, 256), 256, 0, st>>>((const uint4*)in, (uint4*)out, g, n);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "tile_order launch");

@@ -113,10 +113,11 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __rest
 
     uint4 lo[U], hi[U];
     uint32_t mb = 0;
+    const BlockOrigin org = block_origin(g, blockIdx.x);
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         const int unit = tid + 256 * i;              // token = unit >> 3, 16-channel group = unit & 7
-        const uint4* row = token_row<RASTER>(x, g, blk, unit >> 3);
+        const uint4* row = token_row<RASTER>(x, g, org, blockIdx.x, unit >> 3);
         lo[i] = make_uint4(0, 0, 0, 0);
         hi[i] = lo[i];
         if (row) { lo[i] = row[2 * (unit & 7)]; hi[i] = row[2 * (unit & 7) + 1]; }
@@ -165,8 +166,9 @@ __global__ __launch_bounds__(256) void channel_amax_kernel(const uint4* __restri
     if (tid < 128) col[tid] = 0u;
     __syncthreads();
     uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const BlockOrigin org = block_origin(g, blockIdx.x);
     for (int r = tid >> 4; r < g.BS; r += 16) {
-        const uint4* row = token_row<RASTER>(x, g, blockIdx.x, r);
+        const uint4* row = token_row<RASTER>(x, g, org, blockIdx.x, r);
         if (!row) continue;
         const uint4 v = row[c8];
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -198,9 +200,10 @@ __global__ __launch_bounds__(256) void quantize_channels_kernel(const uint4* __r
         sc[tid] = a == 0.0f ? 1.0f : a / 448.0f;
     }
     __syncthreads();
+    const BlockOrigin org = block_origin(g, blockIdx.x);
     for (int unit = tid; unit < BS * 8; unit += 256) {       // 16 channels of one token
         const int r = unit >> 3, c16 = unit & 7;
-        const uint4* row = token_row<RASTER>(x, g, blk, r);
+        const uint4* row = token_row<RASTER>(x, g, org, blockIdx.x, r);
         uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
         if (row) { lo = row[2 * c16]; hi = row[2 * c16 + 1]; }
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};

@@ -24,10 +24,11 @@ OUT_BF16, OUT_F32 = 0, 1
 LAYOUT_TILED, LAYOUT_RASTER = 0, 1
 EDGE_TRUNCATE, EDGE_SHIFT = 0, 1
 
-EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_packed_bytes",
+EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_tile_slots", "fps_packed_bytes",
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
            "fps_quantize_raster",
            "fps_pack_tiles_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
+           "fps_debug_scores_block_q8",
            "fps_attn_fwd")
 
 
@@ -40,7 +41,8 @@ class Window(ctypes.Structure):
 
 
 class Regime(ctypes.Structure):
-    _fields_ = [("prec", ctypes.c_int), ("win", Window)]
+    _fields_ = [("prec", ctypes.c_int), ("win", Window), ("Tt", ctypes.c_int), ("Th", ctypes.c_int),
+                ("Tw", ctypes.c_int)]
 
 
 class StepCfg(ctypes.Structure):
@@ -71,6 +73,8 @@ def lib():
         L.fps_schedule_select.argtypes = [ctypes.POINTER(StepCfg), ctypes.POINTER(Regime)]
         L.fps_num_tiles.restype = ctypes.c_size_t
         L.fps_num_tiles.argtypes = [ctypes.POINTER(Shape)]
+        L.fps_tile_slots.restype = ctypes.c_size_t
+        L.fps_tile_slots.argtypes = [ctypes.POINTER(Shape)]
         L.fps_packed_bytes.restype = ctypes.c_size_t
         L.fps_packed_bytes.argtypes = [ctypes.POINTER(Shape), ip]
         L.fps_tile_mask_host.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), vp,
@@ -83,10 +87,12 @@ def lib():
         L.fps_debug_unpack_q8.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp]
         L.fps_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fps_debug_scores_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, vp, vp]
+        L.fps_debug_scores_block_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, ip, ip, vp,
+                                                ctypes.POINTER(ctypes.c_int), vp]
         L.fps_attn_fwd.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), ip,
                                    ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, ip, vp, vp]
         for name in EXPORTS:
-            if name not in ("fps_last_error", "fps_num_tiles", "fps_packed_bytes"):
+            if name not in ("fps_last_error", "fps_num_tiles", "fps_tile_slots", "fps_packed_bytes"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -106,12 +112,15 @@ def make_shape(heads, grid, tile, B=1, head_dim=128) -> Shape:
 
 
 def make_step_cfg(step, num_steps, alpha1, alpha2, regimes) -> StepCfg:
-    """regimes: three (prec, (wt, wh, ww[, edge])) pairs for the early, mid and late steps (Eq. 6)."""
+    """regimes: three (prec, (wt, wh, ww[, edge])[, (Tt, Th, Tw)]) entries for the early, mid and
+    late steps (Eq. 6); the optional third item is the regime's tile granularity g(t)."""
     cfg = StepCfg()
     cfg.step, cfg.num_steps, cfg.alpha1, cfg.alpha2 = step, num_steps, alpha1, alpha2
-    for i, (prec, win) in enumerate(regimes):
-        cfg.regime[i].prec = prec
-        cfg.regime[i].win = Window(*win)
+    for i, reg in enumerate(regimes):
+        cfg.regime[i].prec = reg[0]
+        cfg.regime[i].win = Window(*reg[1])
+        if len(reg) > 2 and reg[2] is not None:
+            cfg.regime[i].Tt, cfg.regime[i].Th, cfg.regime[i].Tw = reg[2]
     return cfg
 
 
@@ -125,16 +134,23 @@ def _ptr(t):
 
 
 # ---- host helpers ---------------------------------------------------------------------------
-def schedule_select(cfg: StepCfg):
+def schedule_select(cfg: StepCfg, with_tile=False):
+    """(prec, window) of the step's regime; with_tile=True appends its tile (Tt, Th, Tw) or None."""
     out = Regime()
     _check(lib().fps_schedule_select(ctypes.byref(cfg), ctypes.byref(out)))
-    if out.win.edge:
-        return out.prec, (out.win.wt, out.win.wh, out.win.ww, out.win.edge)
-    return out.prec, (out.win.wt, out.win.wh, out.win.ww)
+    win = (out.win.wt, out.win.wh, out.win.ww) + ((out.win.edge,) if out.win.edge else ())
+    if with_tile:
+        return out.prec, win, ((out.Tt, out.Th, out.Tw) if out.Tt else None)
+    return out.prec, win
 
 
 def num_tiles(shape: Shape) -> int:
     return int(lib().fps_num_tiles(ctypes.byref(shape)))
+
+
+def tile_slots(shape: Shape) -> int:
+    """Slots one tile occupies in tiled and packed tensors (its tokens rounded up to whole blocks)."""
+    return int(lib().fps_tile_slots(ctypes.byref(shape)))
 
 
 def packed_bytes(shape: Shape, prec: int) -> int:
@@ -156,10 +172,10 @@ def tile_mask_host(shape: Shape, window):
 
 # ---- device entry points (torch tensors on the current device) --------------------------------
 def _tiled_len(shape: Shape) -> int:
-    nT = -(-shape.T // shape.Tt)
-    nH = -(-shape.H // shape.Th)
-    nW = -(-shape.W // shape.Tw)
-    return nT * nH * nW * shape.Tt * shape.Th * shape.Tw
+    n = num_tiles(shape) * tile_slots(shape)
+    if n == 0:
+        raise FpsError(FPS_ERR_INVALID_ARG, last_error())
+    return n
 
 
 def tile_order(shape: Shape, x_raster, out=None):
@@ -231,10 +247,23 @@ def debug_copy(src, dst):
 
 def debug_scores_q8(shape: Shape, q8, k8, bh, u, v):
     import torch
-    ts = shape.Tt * shape.Th * shape.Tw
+    ts = tile_slots(shape)
     out = torch.empty((ts, ts), dtype=torch.float32, device=q8.device)
     _check(lib().fps_debug_scores_q8(ctypes.byref(shape), _ptr(q8), _ptr(k8), bh, u, v, _ptr(out),
                                      _stream()))
+    return out
+
+
+def debug_scores_block_q8(shape: Shape, q8, k8, bh, u, jq, v, jk, out=None):
+    """Raw score accumulators of one (query block, key block) pair; returns a [BS, BS] tensor."""
+    import torch
+    bs = 32 if tile_slots(shape) % 128 else 128
+    if out is None:
+        out = torch.empty((bs, bs), dtype=torch.float32, device=q8.device)
+    got = ctypes.c_int(0)
+    _check(lib().fps_debug_scores_block_q8(ctypes.byref(shape), _ptr(q8), _ptr(k8), bh, u, jq, v, jk,
+                                           _ptr(out), ctypes.byref(got), _stream()))
+    assert got.value == bs
     return out
 
 

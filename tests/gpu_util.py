@@ -43,6 +43,18 @@ class GpuRun:
         self.raster = [to_device_bf16(a[None]) for a in self.qkv]
         self.tiled = [fps.tile_order(self.shape, r) for r in self.raster]
         self.torch = torch
+        # The library's tiled tensors give every tile TSP >= TS slots (whole blocks); the oracle's
+        # tile order has exactly TS rows per tile.  slots[i] = library slot of oracle row i.
+        self.tsp = fps.tile_slots(self.shape)
+        g = self.g
+        assert self.tsp >= g.TS and fps.num_tiles(self.shape) == g.M
+        self.slots = (np.arange(g.M)[:, None] * self.tsp + np.arange(g.TS)[None, :]).reshape(-1)
+
+    def pad_slots(self):
+        """Boolean mask over the M*TSP library slots: True where the slot holds no real token."""
+        pad = np.ones(self.g.M * self.tsp, dtype=bool)
+        pad[self.slots] = ~fo.valid_tokens(self.g)
+        return pad
 
     def quantize(self, vscale=fps.VSCALE_TILE):
         self.q8 = [fps.quantize_tiles(self.shape, t, r, vscale=vscale) for t, r in zip(self.tiled, (0, 1, 2))]
@@ -78,18 +90,37 @@ class GpuRun:
         return tuple(fo.tile_order(a[head_slot].astype(np.float64), self.g) for a in self.qkv)
 
 
+SCORE_CALL_MAX_SLOTS = 4096      # fps_debug_scores_q8 covers tile pairs up to this many slots
+
+
 def gpu_raw_scores(run: GpuRun, head_slot, part):
     """The kernel's own raw score accumulators for one query tile over its window (valid keys
-    only, same column order as the oracle's parts), fetched through fps_debug_scores_q8."""
+    only, same column order as the oracle's parts), fetched through fps_debug_scores_q8, or block
+    pair by block pair (only blocks that hold real tokens) for tiles too large for that call."""
     g = run.g
     (q8, _), (k8, _), _ = run.q8
     tiles = part["key_tiles"]
-    raw = run.torch.cat([fps.debug_scores_q8(run.shape, q8, k8, head_slot, part["u"], int(v))
-                         for v in tiles], dim=1)
-    run.torch.cuda.synchronize()
-    raw = raw.cpu().numpy()
-    local = np.searchsorted(tiles, part["cols"] // g.TS) * g.TS + part["cols"] % g.TS
-    return raw[:, local]
+    if run.tsp <= SCORE_CALL_MAX_SLOTS:
+        raw = run.torch.cat([fps.debug_scores_q8(run.shape, q8, k8, head_slot, part["u"], int(v))
+                             for v in tiles], dim=1)
+        run.torch.cuda.synchronize()
+        raw = raw.cpu().numpy()
+        local = np.searchsorted(tiles, part["cols"] // g.TS) * run.tsp + part["cols"] % g.TS
+        return raw[:g.TS, local]
+    bs = 128
+    raw = np.zeros((g.TS, part["cols"].size), dtype=np.float32)
+    q_slots = np.flatnonzero(part["rows_valid"])                     # in-tile slots of real query rows
+    k_tile, k_slot = part["cols"] // g.TS, part["cols"] % g.TS
+    buf = run.torch.empty((bs, bs), dtype=run.torch.float32, device="cuda:0")
+    for jq in np.unique(q_slots // bs):
+        rq = q_slots[q_slots // bs == jq]
+        for v in tiles:
+            for jk in np.unique(k_slot[k_tile == v] // bs):
+                sel = np.flatnonzero((k_tile == v) & (k_slot // bs == jk))
+                fps.debug_scores_block_q8(run.shape, q8, k8, head_slot, part["u"], int(jq), int(v), int(jk), out=buf)
+                blk = buf.cpu().numpy()
+                raw[np.ix_(rq, sel)] = blk[np.ix_(rq % bs, k_slot[sel] % bs)]
+    return raw
 
 
 def fp8_tie_slack(run: GpuRun, head_slot, part, ref_rows):
@@ -124,7 +155,8 @@ def fp8_tie_slack(run: GpuRun, head_slot, part, ref_rows):
     return slack, flips, ph_gpu.size
 
 
-def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None, vscale=fps.VSCALE_TILE):
+def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None, vscale=fps.VSCALE_TILE,
+                 reenact=True):
     """Oracle vs GPU for one head (optionally a subset of query tiles).  Returns a dict of
     normalised errors; asserts nothing."""
     g = run.g
@@ -134,16 +166,27 @@ def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None, vs
                               vscale=fo.VSCALE_CHANNEL if vscale == fps.VSCALE_CHANNEL else fo.VSCALE_TILE)
     slack = np.zeros_like(ref)
     flips = elems = 0
-    if prec == fps.PREC_FP8:
+    if prec == fps.PREC_BF16:
+        # BF16 mode rounds every softmax weight to fp16 (relative error <= 2^-12 each) before the
+        # PV product; to first order an output moves by at most 2^-12 * sum_j p_j |v_j| / l.  The
+        # bound matters only where |O| is far above the RMS (a peaked row on a large V value);
+        # 2^-11 leaves a factor two for the fp32 accumulation and the fp32 exp2.
+        for n, part in enumerate(parts):
+            sl = 2.0 ** -11 * (part["p"] @ np.abs(part["v"])) / part["l"][:, None]
+            sl[~part["rows_valid"]] = 0.0
+            slack[n * g.TS:(n + 1) * g.TS] = sl
+    if prec == fps.PREC_FP8 and reenact:
         for n, part in enumerate(parts):
             sl, f, e = fp8_tie_slack(run, head_slot, part, ref[n * g.TS:(n + 1) * g.TS])
             slack[n * g.TS:(n + 1) * g.TS] = sl
             flips += f
             elems += e
     tiles = list(range(g.M)) if q_tiles is None else list(q_tiles)
-    rows = (np.asarray(tiles)[:, None] * g.TS + np.arange(g.TS)[None, :]).reshape(-1)
-    got = out_gpu[0, head_slot][run.torch.from_numpy(rows).to(out_gpu.device)].double().cpu().numpy()
+    rows = (np.asarray(tiles)[:, None] * g.TS + np.arange(g.TS)[None, :]).reshape(-1)   # oracle rows
+    got_all = out_gpu[0, head_slot].double().cpu().numpy()                               # library slots
+    got = got_all[run.slots[rows]]
     valid = fo.valid_tokens(g)[rows]
+    pad_zero = bool(np.all(got[~valid] == 0)) and bool(np.all(got_all[run.pad_slots()] == 0))
     rms = float(np.sqrt(np.mean(ref[valid] ** 2)))
     err = np.abs(got - ref)
     return dict(rms=rms,
@@ -153,7 +196,7 @@ def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None, vs
                 slack_max=float(slack.max() / rms),
                 slack_mean=float(slack[valid].mean() / rms),
                 flips=flips, p_elems=elems,
-                pad_rows_zero=bool(np.all(got[~valid] == 0)),
+                pad_rows_zero=pad_zero,
                 finite=bool(np.all(np.isfinite(got))))
 
 
@@ -190,4 +233,6 @@ def score_error_ratio(run: GpuRun, head_slot, u, v):
     got = fps.debug_scores_q8(run.shape, q8, k8, head_slot, u, v)
     run.torch.cuda.synchronize()
     got = got.double().cpu().numpy()
+    assert np.all(got[g.TS:] == 0) and np.all(got[:, g.TS:] == 0)   # padding slots: zero codes
+    got = got[:g.TS, :g.TS]
     return float(np.max(np.abs(got - exact) / np.maximum(absdot, 1e-30))), got, exact

@@ -33,6 +33,15 @@ def test_schedule_select_matches_oracle():
             assert (prec, win) == want
     picks = [fps.schedule_select(fps.make_step_cfg(t, 50, 0.2, 0.5, regimes))[1] for t in range(1, 51)]
     assert picks == [(41, 11, 9)] * 10 + [(7, 5, 5)] * 15 + [(3, 3, 3)] * 25
+    # Eq. 6 pairs each window with a tile granularity g(t): coarse, fine, intermediate
+    with_g = [(fps.PREC_FP8, (3, 3, 3), (6, 8, 8)), (fps.PREC_FP8, (7, 5, 5), (1, 8, 16)),
+              (fps.PREC_FP8, (5, 3, 3), (2, 8, 16))]
+    tiles = [fps.schedule_select(fps.make_step_cfg(t, 50, 0.2, 0.5, with_g), with_tile=True)[2]
+             for t in range(1, 51)]
+    assert tiles == [(6, 8, 8)] * 10 + [(1, 8, 16)] * 15 + [(2, 8, 16)] * 25
+    assert fps.schedule_select(fps.make_step_cfg(3, 50, 0.2, 0.5, regimes), with_tile=True)[2] is None
+    with pytest.raises(fps.FpsError):
+        fps.schedule_select(fps.make_step_cfg(3, 50, 0.2, 0.5, [(1, (3, 3, 3), (6, 0, 8))] * 3))
 
 
 @pytest.mark.parametrize("bad", [dict(step=0), dict(step=51), dict(alpha1=0.6), dict(alpha2=1.0),
@@ -74,15 +83,18 @@ def test_shape_validation():
     assert fps.num_tiles(ok) == 32
     assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 4, 4), head_dim=64)) == 0
     assert "head_dim" in fps.last_error()
-    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (1, 4, 4))) == 0      # 16-token tiles
+    # any tile shape up to 32768 tokens; a tile occupies whole blocks of 32 or 128 slots
+    for tile, m, slots in [((1, 4, 4), 64, 32), ((2, 4, 4), 32, 32), ((3, 4, 4), 32, 64),
+                           ((2, 8, 4), 16, 64), ((1, 8, 12), 16, 96), ((1, 7, 15), 24, 128),
+                           ((1, 8, 16), 8, 128), ((2, 8, 12), 8, 256), ((2, 8, 16), 4, 256),
+                           ((6, 8, 8), 4, 384), ((4, 16, 16), 1, 1024), ((12, 16, 16), 1, 3072),
+                           ((24, 32, 32), 1, 24576), ((32, 32, 32), 1, 32768)]:
+        sh = fps.make_shape(2, (4, 16, 16), tile)
+        assert (fps.num_tiles(sh), fps.tile_slots(sh)) == (m, slots), tile
+        assert fps.packed_bytes(sh, fps.PREC_FP8) == 2 * m * slots * 128
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (33, 32, 32))) == 0   # 33792 tokens: too large
     assert "unsupported" in fps.last_error()
-    # tiles of several 128-token blocks: any multiple of 128 up to 1024 tokens
-    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 8, 16))) == 4     # 256-token tiles
-    assert fps.num_tiles(fps.make_shape(2, (6, 16, 16), (6, 8, 8))) == 4      # 384
-    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (4, 16, 16))) == 1    # 1024
-    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 8, 12))) == 0     # 192: not a multiple
-    assert fps.num_tiles(fps.make_shape(2, (8, 16, 16), (8, 16, 16))) == 0    # 2048: too large
-    assert "unsupported" in fps.last_error()
+    assert fps.tile_slots(fps.make_shape(2, (4, 16, 16), (33, 32, 32))) == 0
     assert fps.num_tiles(fps.make_shape(0, (4, 16, 16), (2, 4, 4))) == 0
     assert L.fps_num_tiles(None) == 0
 
@@ -119,7 +131,13 @@ def test_device_entry_points_validate_before_launching():
     assert L.fps_quantize_raster(S, good, 0, 0, None, good, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_copy(good, good, 24, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_copy(good, None, 32, None) == fps.FPS_ERR_INVALID_ARG
-    big = fps.make_shape(2, (4, 16, 16), (2, 8, 4))                             # 64-token tiles
+    big = fps.make_shape(2, (64, 64, 64), (64, 32, 32))                         # 65536-token tiles
     assert L.fps_attn_fwd(ctypes.byref(big), ctypes.byref(win), 1, None, *args) == fps.FPS_ERR_UNSUPPORTED
+    big = fps.make_shape(2, (24, 32, 32), (24, 32, 32))        # score debug call: at most 4096 slots
+    assert L.fps_debug_scores_q8(ctypes.byref(big), good, good, 0, 0, 0, good, None) == fps.FPS_ERR_UNSUPPORTED
     cfg = fps.make_step_cfg(99, 50, 0.2, 0.5, [(1, (3, 3, 3))] * 3)
     assert L.fps_attn_fwd(S, None, 1, ctypes.byref(cfg), *args) == fps.FPS_ERR_INVALID_ARG
+    # a regime that names a tile must be called with inputs of that tile
+    cfg = fps.make_step_cfg(5, 50, 0.2, 0.5, [(1, (3, 3, 3), (shape.Tt + 1, shape.Th, shape.Tw))] * 3)
+    assert L.fps_attn_fwd(S, None, 1, ctypes.byref(cfg), *args) == fps.FPS_ERR_INVALID_ARG
+    assert "selects tile" in fps.last_error()

@@ -26,7 +26,9 @@ def tiny():
 # ---- layout and quantisation: bit exact -----------------------------------------------------
 @pytest.mark.parametrize("grid,tile", [((4, 16, 16), (2, 4, 4)), ((3, 5, 6), (2, 4, 4)),
                                        ((2, 9, 20), (1, 8, 16)), ((3, 7, 9), (2, 4, 16)),
-                                       ((3, 13, 20), (2, 8, 16)), ((7, 9, 10), (6, 8, 8))])
+                                       ((3, 13, 20), (2, 8, 16)), ((7, 9, 10), (6, 8, 8)),
+                                       ((5, 7, 9), (3, 4, 4)), ((2, 9, 20), (1, 7, 15)),
+                                       ((3, 5, 6), (2, 8, 4))])
 def test_tile_order_roundtrip_bit_exact(grid, tile):
     import torch
     say("tile_order", grid, tile)
@@ -35,7 +37,8 @@ def test_tile_order_roundtrip_bit_exact(grid, tile):
     for a, t in zip(run.qkv, run.tiled):
         want = fo.tile_order(a, run.g)
         got = t[0].float().cpu().numpy()
-        assert np.array_equal(got, want)
+        assert np.array_equal(got[:, run.slots], want)
+        assert np.all(got[:, run.pad_slots()] == 0)
         back = fps.tile_unorder(run.shape, t)
         assert np.array_equal(back[0].float().cpu().numpy(), a)
         back32 = fps.tile_unorder(run.shape, t.float().contiguous())
@@ -51,9 +54,11 @@ def _check_quantize(run, heads_slots, label):
             x = fo.tile_order(run.qkv[role][hs].astype(np.float64), g)
             wc, ws = fo.quantize_tiles(x, g)
             assert np.array_equal(sc[hs].view(np.uint32), ws.view(np.uint32)), (label, role, hs)
-            zero_sign = ((codes[hs] ^ wc) == 0x80) & ((wc & 0x7F) == 0)
-            mism = (codes[hs] != wc) & ~zero_sign
+            got = codes[hs][run.slots]
+            zero_sign = ((got ^ wc) == 0x80) & ((wc & 0x7F) == 0)
+            mism = (got != wc) & ~zero_sign
             assert int(mism.sum()) == 0, (label, role, hs, int(mism.sum()))
+            assert np.all((codes[hs][run.pad_slots()] & 0x7F) == 0)
         assert not np.any((codes & 0x7F) == 0x7F)
 
 
@@ -70,7 +75,11 @@ def test_quantize_ragged_128_token_tiles_bit_exact():
 
 @pytest.mark.parametrize("grid,tile", [((3, 13, 20), (2, 8, 16)),      # 256 tokens; last T tile half empty
                                        ((7, 9, 10), (6, 8, 8)),         # 384 tokens, ragged on every axis
-                                       ((5, 16, 20), (4, 16, 16))])     # 1024 tokens, the largest tile
+                                       ((5, 16, 20), (4, 16, 16)),      # 1024 tokens
+                                       ((5, 7, 9), (3, 4, 4)),          # 48 tokens in two 32-slot blocks
+                                       ((2, 9, 20), (1, 7, 15)),        # 105 tokens in one 128-slot block
+                                       ((13, 17, 20), (12, 16, 16)),    # 3072 tokens, 24 blocks
+                                       ((25, 5, 6), (24, 32, 32))])     # 24576 tokens, 192 blocks, mostly padding
 def test_quantize_tiles_of_several_blocks_bit_exact(grid, tile):
     """One scale per TILE although the kernels work on 128-token blocks (tile amax pre-pass)."""
     say("quantize multi-block", grid, tile)
@@ -184,7 +193,11 @@ def test_attention_tiny_fp8_windows(tiny, window):
     ((5, 8, 16), (1, 8, 16), (2, 1, 1)),        # temporal-only window, even size
     ((3, 13, 20), (2, 8, 16), (3, 3, 3)),       # 256-token tiles (2 blocks); one key block all padding
     ((7, 9, 10), (6, 8, 8), (3, 1, 3)),         # 384-token tiles (3 blocks), ragged on every axis
-    ((5, 16, 20), (4, 16, 16), (3, 1, 1)),      # 1024-token tiles (8 blocks), the largest supported
+    ((5, 16, 20), (4, 16, 16), (3, 1, 1)),      # 1024-token tiles (8 blocks)
+    ((5, 7, 9), (3, 4, 4), (3, 3, 3)),          # 48-token tiles: two 32-slot blocks, 16 slots of padding
+    ((3, 5, 12), (2, 8, 4), (3, 1, 3)),         # 64-token tiles: two 32-slot blocks
+    ((2, 9, 20), (1, 7, 15), (3, 3, 3)),        # 105-token tiles in one 128-slot block
+    ((13, 17, 20), (12, 16, 16), (3, 3, 3)),    # 3072-token tiles (24 blocks); skipped padding-only blocks
 ])
 def test_attention_small_shapes(prec, grid, tile, window):
     say("attention small", prec, grid, tile, window)
@@ -217,8 +230,9 @@ def test_per_channel_v_scales(grid, tile, window):
     for h in range(2):
         wc, ws = fo.quantize_channels(fo.tile_order(run.qkv[2][h].astype(np.float64), run.g))
         assert np.array_equal(sc[0, h].cpu().numpy(), ws)
-        zero_sign = ((codes[h] ^ wc) == 0x80) & ((wc & 0x7F) == 0)
-        assert int(((codes[h] != wc) & ~zero_sign).sum()) == 0
+        got = codes[h][run.slots]
+        zero_sign = ((got ^ wc) == 0x80) & ((wc & 0x7F) == 0)
+        assert int(((got != wc) & ~zero_sign).sum()) == 0
     out = run.attn(fps.PREC_FP8, vscale=fps.VSCALE_CHANNEL)
     for h in range(2):
         st = gu.compare_head(run, out, h, fps.PREC_FP8, window, vscale=fps.VSCALE_CHANNEL)
@@ -273,7 +287,7 @@ def test_garbage_in_padded_slots_cannot_leak():
                             n_outlier=3, config_id=9)
     run = gu.GpuRun(w)
     clean = run.attn(fps.PREC_FP8).clone()
-    pad = torch.from_numpy(~fo.valid_tokens(run.g)).to("cuda:0")
+    pad = torch.from_numpy(run.pad_slots()).to("cuda:0")
     for t in run.tiled:
         t[0, 0, pad] = 0.0078125                        # small: cannot raise any tile's amax
     del run.q8
@@ -332,6 +346,47 @@ def test_step_config_selects_regime(tiny):
         assert torch.equal(want, got)
 
 
+def test_largest_granularity_of_the_tile_size_ablation():
+    """(24,32,32) tiles (Table 3's largest): 24576 slots per tile, 192 blocks; the comparator
+    fetches the kernel's scores block pair by block pair."""
+    say("24x32x32 tiles")
+    w = dataclasses.replace(synth.TINY, grid=(25, 5, 6), tile=(24, 32, 32), window=(3, 1, 1), heads=1,
+                            n_outlier=3, config_id=16)
+    run = gu.GpuRun(w)
+    assert run.tsp == 24576 and run.g.M == 2
+    for prec in (fps.PREC_BF16, fps.PREC_FP8):
+        out, vis = run.attn(prec, visited=True)
+        assert np.array_equal(vis.cpu().numpy().astype(bool), fo.tile_mask(run.g, w.window))
+        st = gu.compare_head(run, out, 0, prec, w.window)
+        say("  ", prec, st)
+        gu.assert_parity(st, f"24x32x32 prec {prec}")
+
+
+def test_step_config_with_granularity_per_regime():
+    """Eq. 6: every regime has its own tile granularity g(t) and window W(t).  The caller
+    quantises with the tile of the step's regime; a call whose inputs have another tile is
+    refused."""
+    say("step config with g(t)")
+    regimes = [(fps.PREC_FP8, (1, 1, 3), (6, 8, 8)),        # early: coarse tiles, sparse window
+               (fps.PREC_FP8, (3, 3, 3), (1, 8, 16)),       # mid: fine tiles, dense window
+               (fps.PREC_FP8, (1, 3, 3), (2, 8, 16))]       # late: in between
+    runs = {}
+    for step, idx in ((3, 0), (20, 1), (44, 2)):
+        cfg = fps.make_step_cfg(step, 50, 0.2, 0.5, regimes)
+        prec, win, tile = fps.schedule_select(cfg, with_tile=True)
+        assert (prec, win, tile) == regimes[idx]
+        w = dataclasses.replace(synth.TINY, grid=(7, 13, 20), tile=tile, window=win, heads=1,
+                                n_outlier=3, config_id=17)
+        run = runs[idx] = gu.GpuRun(w)
+        out = run.attn(prec, window=(9, 9, 9), step=cfg)     # the explicit window is overridden
+        st = gu.compare_head(run, out, 0, prec, win)
+        say("  step", step, tile, win, st)
+        gu.assert_parity(st, f"step {step}")
+    with pytest.raises(fps.FpsError) as e:                   # inputs of the late regime at an early step
+        runs[2].attn(fps.PREC_FP8, step=fps.make_step_cfg(3, 50, 0.2, 0.5, regimes))
+    assert e.value.status == fps.FPS_ERR_INVALID_ARG
+
+
 # ---- full-size shapes, sampled against the oracle ---------------------------------------------
 def _sampled_parity(w, prec, window, head_picks, seed, n_interior=2):
     run = gu.GpuRun(w)
@@ -359,7 +414,7 @@ def test_wan_1_3b_480p_fp8_sampled():
             ws = fo.tile_scales(fo.tile_order(run.qkv[role][h], run.g), run.g)
             assert np.array_equal(sc[h], ws)
         h = (5, 0, 11)[role]
-        codes = fps.debug_unpack_q8(run.shape, xq, role)[0, h].cpu().numpy()
+        codes = fps.debug_unpack_q8(run.shape, xq, role)[0, h].cpu().numpy()[run.slots]
         wc, _ = fo.quantize_tiles(fo.tile_order(run.qkv[role][h].astype(np.float64), run.g), run.g)
         zero_sign = ((codes ^ wc) == 0x80) & ((wc & 0x7F) == 0)
         assert int(((codes != wc) & ~zero_sign).sum()) == 0, (role, h)
