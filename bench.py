@@ -7,6 +7,7 @@ fused kernel per tensor) and the sliding-tile attention kernel, whose epilogue w
 back in raster order.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-dense] [--no-cpu]
+                  [--schedule] [--variants]
 """
 import argparse
 import json
@@ -47,6 +48,9 @@ def main():
                     help="also launch one plain 1 GiB device copy (reference for the profiler's traffic counters)")
     ap.add_argument("--schedule", action="store_true",
                     help="also run the 50-call denoising-step-aware schedule (Eq. 6) on fresh inputs per call")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the variants of the path on the same grid: per-channel V scales, BF16 with "
+                         "the sparse window, the shifted-window edge rule, other tile shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads shard across GPUs without any "
@@ -73,7 +77,7 @@ def main():
     gen_s = time.time() - t0
 
     # persistent buffers: the timed region allocates nothing
-    L = M * TS
+    L = M * fps.tile_slots(shape)
     packed = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device=dev) for _ in range(3)]
     scales = [torch.empty((1, w.heads, M), dtype=torch.float32, device=dev) for _ in range(3)]
     out_raster = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.bfloat16, device=dev)
@@ -164,6 +168,9 @@ def main():
         result["speedup_vs_own_dense_bf16"] = {"attention_only": bf16_ms / attn_ms,
                                                "with_quantize": bf16_ms / (attn_ms + quant_ms)}
 
+    if args.variants:
+        result["variants"] = run_variants(w, raster, dev)
+
     if args.schedule:
         del raster
         result["schedule"] = run_schedule(w, shape, dev)
@@ -172,6 +179,89 @@ def main():
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_heads, TS)
 
     print(json.dumps(result))
+
+
+def run_variants(w, raster, dev, reps=5):
+    """Variants of the hot path on the workload's grid and inputs, each timed as a whole (operand
+    preparation from the raster tensors + attention with raster output): the paper's per-channel V
+    scales, BF16 operands with the same sparse window, the shifted-window edge rule, and other tile
+    shapes (the tile is the quantisation group and the sparsity unit; windows chosen to cover about
+    the same token neighbourhood as the workload's own).  TFLOP/s counts 4*TS^2*d per kept tile pair
+    with TS the tile's TOKENS (padding slots of a tile that is not a whole number of blocks are
+    executed but not counted)."""
+    import torch
+    from paper_2506_04648_amd import fps
+    out = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.bfloat16, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def fp8_case(name, tile, window, vscale=fps.VSCALE_TILE):
+        shape = fps.make_shape(w.heads, w.grid, tile)
+        M = fps.num_tiles(shape)
+        packed = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device=dev) for _ in range(3)]
+        scales = [torch.empty((1, w.heads, 128 if (i == 2 and vscale == fps.VSCALE_CHANNEL) else M),
+                              dtype=torch.float32, device=dev) for i in range(3)]
+
+        def prep():
+            for i in range(3):
+                fps.quantize_tiles(shape, raster[i], i, vscale=vscale, out=packed[i], scales=scales[i], raster=True)
+
+        def attn():
+            fps.attn_fwd(shape, window, fps.PREC_FP8, packed[0], packed[1], packed[2], scales[0], scales[1],
+                         scales[2], vscale=vscale, out=out, raster_out=True)
+        prep_ms = timed(prep)
+        attn_ms = timed(attn)
+        return record(name, shape, tile, window, prep_ms, attn_ms, "fp8")
+
+    def bf16_case(name, tile, window):
+        shape = fps.make_shape(w.heads, w.grid, tile)
+        M = fps.num_tiles(shape)
+        L = M * fps.tile_slots(shape)
+        tiled = torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev)
+        packed = [torch.empty(fps.packed_bytes(shape, fps.PREC_BF16), dtype=torch.uint8, device=dev) for _ in range(3)]
+        vs = torch.empty((1, w.heads, M), dtype=torch.float32, device=dev)
+
+        def prep():
+            for i in range(3):
+                fps.tile_order(shape, raster[i], out=tiled)
+                fps.pack_tiles_bf16(shape, tiled, i, out=packed[i], vscale=vs)
+
+        def attn():
+            fps.attn_fwd(shape, window, fps.PREC_BF16, packed[0], packed[1], packed[2], sv=vs, out=out,
+                         raster_out=True)
+        prep_ms = timed(prep)
+        attn_ms = timed(attn)
+        return record(name, shape, tile, window, prep_ms, attn_ms, "bf16")
+
+    def record(name, shape, tile, window, prep_ms, attn_ms, prec):
+        _, pairs = fps.tile_mask_host(shape, window)
+        ts = tile[0] * tile[1] * tile[2]
+        flop = pairs * w.heads * 4.0 * ts * ts * w.head_dim
+        return {"name": name, "precision": prec, "tile": list(tile), "tile_tokens": ts,
+                "tile_slots": fps.tile_slots(shape), "window": list(window), "kept_tile_pairs": pairs,
+                "prepare_ms": prep_ms, "attention_ms": attn_ms,
+                "attention_tflops": flop / attn_ms / 1e9, "whole_path_tflops": flop / (prep_ms + attn_ms) / 1e9}
+
+    base, win = tuple(w.tile), tuple(w.window)
+    rows = [fp8_case("per-tile V scales (the workload itself)", base, win),
+            fp8_case("per-channel V scales (Sec. 3.2)", base, win, vscale=fps.VSCALE_CHANNEL),
+            bf16_case("BF16 operands, same sparse window", base, win),
+            fp8_case("shifted-window edge rule", base, win + (fps.EDGE_SHIFT,)),
+            fp8_case("tile (2,8,16): 256 tokens, 2 blocks", (2, 8, 16), (3, 3, 3)),
+            fp8_case("tile (6,8,8): 384 tokens, 3 blocks", (6, 8, 8), (1, 3, 5)),
+            fp8_case("tile (3,4,4): 48 tokens in two 32-slot blocks", (3, 4, 4), (1, 7, 13)),
+            fp8_case("tile (12,16,16): 3072 tokens, 24 blocks", (12, 16, 16), (1, 1, 3))]
+    return rows
 
 
 def run_schedule(w, shape, dev, num_steps=50, alpha1=0.2, alpha2=0.5):
@@ -194,7 +284,7 @@ def run_schedule(w, shape, dev, num_steps=50, alpha1=0.2, alpha2=0.5):
         del q, k, v
     gen_s = time.time() - t0
     M = fps.num_tiles(shape)
-    L = M * TS
+    L = M * fps.tile_slots(shape)
     packed8 = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device=dev) for _ in range(3)]
     packed16 = [torch.empty(fps.packed_bytes(shape, fps.PREC_BF16), dtype=torch.uint8, device=dev) for _ in range(3)]
     tiled = [torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev) for _ in range(3)]

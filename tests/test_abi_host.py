@@ -62,6 +62,10 @@ def test_schedule_select_rejects_bad_config(bad):
     ((21, 45, 80), (1, 8, 16), (5, 3, 3)),
     ((21, 45, 80), (1, 8, 16), (6, 6, 1)),
     ((5, 9, 33), (2, 4, 4), (2, 5, 100)),
+    ((21, 30, 52), (3, 4, 4), (3, 5, 5)),          # tile shapes of the granularity ablation (Table 3)
+    ((21, 30, 52), (6, 8, 8), (3, 3, 3)),
+    ((21, 45, 80), (12, 16, 16), (1, 3, 3)),
+    ((21, 45, 80), (24, 32, 32), (3, 3, 3)),
 ])
 def test_tile_mask_host_matches_oracle(grid, tile, window):
     shape = fps.make_shape(2, grid, tile)
@@ -73,8 +77,10 @@ def test_tile_mask_host_matches_oracle(grid, tile, window):
     mask_s, pairs_s = fps.tile_mask_host(shape, window + (fps.EDGE_SHIFT,))
     want_s = fo.tile_mask(g, window, edge=fo.EDGE_SHIFT)
     assert np.array_equal(mask_s.astype(bool), want_s) and pairs_s == int(want_s.sum())
-    assert fps.packed_bytes(shape, fps.PREC_FP8) == 2 * g.L_padded * 128
-    assert fps.packed_bytes(shape, fps.PREC_BF16) == 4 * g.L_padded * 128
+    slots = fps.tile_slots(shape)                      # a tile's tokens rounded up to whole blocks
+    assert slots >= g.TS and slots % 32 == 0 and slots - g.TS < 128
+    assert fps.packed_bytes(shape, fps.PREC_FP8) == 2 * g.M * slots * 128
+    assert fps.packed_bytes(shape, fps.PREC_BF16) == 4 * g.M * slots * 128
 
 
 def test_shape_validation():

@@ -333,6 +333,70 @@ def test_two_runs_are_bit_identical(tiny):
     assert torch.equal(a, b)
 
 
+def test_batch_and_heads_are_interchangeable():
+    """Tensors are indexed by b*heads + h: (B=2, heads=3) equals (B=1, heads=6) bit for bit."""
+    import torch
+    say("batch")
+    w = dataclasses.replace(synth.TINY, grid=(2, 13, 40), tile=(1, 8, 16), window=(3, 3, 3), heads=6,
+                            n_outlier=3, config_id=18)
+    run = gu.GpuRun(w)
+    flat = fps.make_shape(6, w.grid, w.tile, B=1)
+    two = fps.make_shape(3, w.grid, w.tile, B=2)
+    outs = []
+    for sh, lead in ((flat, (1, 6)), (two, (2, 3))):
+        x = [r.reshape(lead + r.shape[2:]) for r in run.raster]
+        q8 = [fps.quantize_tiles(sh, x[i], i, raster=True) for i in range(3)]
+        assert q8[0][1].shape == lead + (run.g.M,)
+        o = fps.attn_fwd(sh, w.window, fps.PREC_FP8, q8[0][0], q8[1][0], q8[2][0], q8[0][1], q8[1][1],
+                         q8[2][1], out_dtype=torch.float32, raster_out=True)
+        assert o.shape == lead + tuple(w.grid) + (128,)
+        outs.append(o.reshape(-1))
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1])
+
+
+def test_side_stream_and_graph_replay(tiny):
+    """The library launches on the stream it is given and allocates nothing, so the whole path
+    (three fused quantise passes + attention) can run on a side stream and be captured into a HIP
+    graph; every replay, with eager work and synchronisations in between, reproduces the eager
+    result bit for bit."""
+    import torch
+    say("stream + graph")
+    shape, w = tiny.shape, tiny.w
+    M = tiny.g.M
+    packed = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device="cuda:0") for _ in range(3)]
+    scales = [torch.empty((1, w.heads, M), dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    out = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.float32, device="cuda:0")
+
+    def path():
+        for i in range(3):
+            fps.quantize_tiles(shape, tiny.raster[i], i, out=packed[i], scales=scales[i], raster=True)
+        fps.attn_fwd(shape, w.window, fps.PREC_FP8, packed[0], packed[1], packed[2], scales[0], scales[1],
+                     scales[2], out=out, raster_out=True)
+
+    path()
+    torch.cuda.synchronize()
+    want = out.clone()
+    side = torch.cuda.Stream()                      # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    out.zero_()
+    with torch.cuda.stream(side):
+        path()
+    side.synchronize()
+    assert torch.equal(out, want)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    for rep in range(4):
+        out.fill_(float(rep))                        # eager work between the replays
+        for p_ in packed:
+            p_.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), rep
+
+
 def test_step_config_selects_regime(tiny):
     import torch
     say("step config")
