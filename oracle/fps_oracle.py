@@ -43,13 +43,41 @@ VSCALE_CHANNEL = 1  # one V scale per channel over all tokens (the paper's Sec. 
 
 @dataclasses.dataclass(frozen=True)
 class Geometry:
-    """Token grid (T,H,W), tile (Tt,Th,Tw) and everything derived from them (Sec. 3.1)."""
+    """Token grid (T,H,W), tile (Tt,Th,Tw) and everything derived from them (Sec. 3.1).
+
+    (Qt,Qh,Qw), if given, is the quantisation granularity g (Sec. 3.3 names g(t) and W(t) as
+    separate hyper-parameters): each tile is cut into sub-tiles of that shape, which must divide
+    the tile, and every sub-tile has its own scale, while the window of Eq. 2 keeps counting in
+    whole tiles.  The default (0,0,0) is the unified granularity: one scale per tile."""
     T: int
     H: int
     W: int
     Tt: int
     Th: int
     Tw: int
+    Qt: int = 0
+    Qh: int = 0
+    Qw: int = 0
+
+    def __post_init__(self):
+        qt, qh, qw = self.qtile
+        assert self.Tt % qt == 0 and self.Th % qh == 0 and self.Tw % qw == 0, "sub-tile must divide the tile"
+
+    @property
+    def qtile(self):
+        if self.Qt == 0 and self.Qh == 0 and self.Qw == 0:
+            return (self.Tt, self.Th, self.Tw)
+        return (self.Qt, self.Qh, self.Qw)
+
+    @property
+    def NS(self):
+        """Quantisation groups (sub-tiles) per tile."""
+        qt, qh, qw = self.qtile
+        return (self.Tt // qt) * (self.Th // qh) * (self.Tw // qw)
+
+    @property
+    def n_groups(self):
+        return self.M * self.NS
 
     @property
     def n_tiles_axis(self):
@@ -107,6 +135,17 @@ def tile_unorder(y: np.ndarray, g: Geometry) -> np.ndarray:
     return y[..., token_positions(g), :].reshape(lead + (g.T, g.H, g.W, y.shape[-1]))
 
 
+def group_of_slot(g: Geometry) -> np.ndarray:
+    """int [M*TS]: the quantisation group of every tile-ordered slot.  Slot (u, r) with in-tile
+    coordinates (rt,rh,rw) belongs to sub-tile s = ((rt//Qt)*(Th//Qh) + rh//Qh)*(Tw//Qw) + rw//Qw
+    of tile u, group u*NS + s.  With the unified granularity this is just the tile index."""
+    qt, qh, qw = g.qtile
+    r = np.arange(g.TS)
+    rw, rh, rt = r % g.Tw, (r // g.Tw) % g.Th, r // (g.Tw * g.Th)
+    s = ((rt // qt) * (g.Th // qh) + rh // qh) * (g.Tw // qw) + rw // qw
+    return (np.arange(g.M)[:, None] * g.NS + s[None, :]).reshape(-1)
+
+
 def valid_tokens(g: Geometry) -> np.ndarray:
     """bool [M*TS]: True where the tile-ordered slot holds a real token (t<T, h<H, w<W)."""
     v = np.zeros(g.L_padded, dtype=bool)
@@ -161,11 +200,19 @@ def _scale_from_amax(amax: np.ndarray) -> np.ndarray:
 
 
 def tile_scales(x_tiled: np.ndarray, g: Geometry) -> np.ndarray:
-    """[..., M*TS, d] -> float32 [..., M]: Eq. 4, max over all TS*d entries of the tile."""
+    """[..., M*TS, d] -> float32 [..., M*NS]: Eq. 4, max over all entries of each quantisation
+    group (the whole tile, TS*d entries, unless the geometry names a finer sub-tile)."""
     lead = x_tiled.shape[:-2]
     d = x_tiled.shape[-1]
-    amax = np.abs(x_tiled.reshape(lead + (g.M, g.TS * d))).max(axis=-1)
-    return _scale_from_amax(amax)
+    if g.NS == 1:
+        amax = np.abs(x_tiled.reshape(lead + (g.M, g.TS * d))).max(axis=-1)
+        return _scale_from_amax(amax)
+    grp = group_of_slot(g)
+    row_amax = np.abs(x_tiled).max(axis=-1).reshape((-1, g.L_padded))
+    amax = np.zeros((row_amax.shape[0], g.n_groups), dtype=row_amax.dtype)
+    for b in range(row_amax.shape[0]):
+        np.maximum.at(amax[b], grp, row_amax[b])
+    return _scale_from_amax(amax.reshape(lead + (g.n_groups,)))
 
 
 def channel_scales(x_tiled: np.ndarray) -> np.ndarray:
@@ -174,16 +221,26 @@ def channel_scales(x_tiled: np.ndarray) -> np.ndarray:
 
 
 def quantize_tiles(x_tiled: np.ndarray, g: Geometry):
-    """Per-tile scales and e4m3 codes.  Returns (codes uint8 [..., M*TS, d], scales f32 [..., M])."""
+    """Per-group scales and e4m3 codes.  Returns (codes uint8 [..., M*TS, d], scales f32 [..., M*NS])."""
     scales = tile_scales(x_tiled, g)
     lead = x_tiled.shape[:-2]
     d = x_tiled.shape[-1]
-    xt = x_tiled.reshape((-1, g.M, g.TS * d))
-    sc = scales.reshape((-1, g.M))
+    if g.NS == 1:
+        xt = x_tiled.reshape((-1, g.M, g.TS * d))
+        sc = scales.reshape((-1, g.M))
+        codes = np.empty(xt.shape, dtype=np.uint8)
+        for b in range(xt.shape[0]):
+            for u in range(g.M):
+                codes[b, u] = e4m3.encode_scaled(xt[b, u], sc[b, u])
+        return codes.reshape(lead + (g.L_padded, d)), scales
+    grp = group_of_slot(g)
+    members = [np.flatnonzero(grp == i) for i in range(g.n_groups)]
+    xt = x_tiled.reshape((-1, g.L_padded, d))
+    sc = scales.reshape((-1, g.n_groups))
     codes = np.empty(xt.shape, dtype=np.uint8)
     for b in range(xt.shape[0]):
-        for u in range(g.M):
-            codes[b, u] = e4m3.encode_scaled(xt[b, u], sc[b, u])
+        for i, rows in enumerate(members):
+            codes[b, rows] = e4m3.encode_scaled(xt[b, rows], sc[b, i])
     return codes.reshape(lead + (g.L_padded, d)), scales
 
 
@@ -236,6 +293,7 @@ def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vsc
     q_tiles = list(range(M)) if q_tiles is None else list(q_tiles)
     keep = tile_mask(g, window)
     valid = valid_tokens(g)
+    grp = group_of_slot(g)                                   # quantisation group of every slot
     c_scale = LOG2E / math.sqrt(d)
 
     if prec == PREC_FP8:
@@ -244,7 +302,7 @@ def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vsc
         qh, kh = e4m3.decode(qc), e4m3.decode(kc)           # unscaled code values
         if vscale == VSCALE_TILE:
             vc, sv = quantize_tiles(np.asarray(v_tiled, dtype=np.float64), g)
-            vh = e4m3.decode(vc) * np.repeat(sv.astype(np.float64), TS)[:, None]
+            vh = e4m3.decode(vc) * sv.astype(np.float64)[grp][:, None]
         else:
             vc, sv = quantize_channels(np.asarray(v_tiled, dtype=np.float64))
             vh = e4m3.decode(vc) * sv.astype(np.float64)[None, :]
@@ -254,8 +312,8 @@ def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vsc
         qh = np.asarray(q_tiled, dtype=np.float64)
         kh = np.asarray(k_tiled, dtype=np.float64)
         vh = np.asarray(v_tiled, dtype=np.float64)
-        sq = np.ones(M)
-        sk = np.ones(M)
+        sq = np.ones(g.n_groups)
+        sk = np.ones(g.n_groups)
 
     out = np.zeros((len(q_tiles) * TS, d), dtype=np.float64)
     parts = []
@@ -265,9 +323,10 @@ def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vsc
         cols = cols[valid[cols]]                              # padded keys never take part
         Qu = qh[u * TS:(u + 1) * TS]
         Kw = kh[cols]
-        # S' = (q.k) * s^Q_u * s^K_v * log2(e)/sqrt(d): scores dequantised per tile pair, base 2
+        # S' = (q.k) * s^Q * s^K * log2(e)/sqrt(d): scores dequantised per pair of quantisation
+        # groups (per tile pair under the unified granularity), base 2
         raw = Qu @ Kw.T
-        pair_scale = (sq[u] * sk[cols // TS] * c_scale)[None, :]
+        pair_scale = sq[grp[u * TS:(u + 1) * TS]][:, None] * sk[grp[cols]][None, :] * c_scale
         S = raw * pair_scale
         m = np.ceil(S.max(axis=1))                            # integer row reference
         p = np.exp2(S - m[:, None])                           # un-normalised P in (0, 1]

@@ -78,13 +78,16 @@ def quantize_raster(x, tile, per_channel=False):
     return out, scales
 
 
-def attention_raster(q, k, v, tile, window, fp8, v_per_channel=False):
-    """One head, raster [T,H,W,d] float64 in and out."""
+def attention_raster(q, k, v, tile, window, fp8, v_per_channel=False, qtile=None):
+    """One head, raster [T,H,W,d] float64 in and out.  qtile: quantisation sub-tile (it divides
+    the tile, so the sub-tiles of all tiles together are simply the grid cut into qtile boxes);
+    the window keeps counting in whole tiles."""
     T, H, W, d = q.shape
     if fp8:
-        qh, _ = quantize_raster(q, tile)
-        kh, _ = quantize_raster(k, tile)
-        vh, _ = quantize_raster(v, tile, per_channel=v_per_channel)
+        qt = tile if qtile is None else qtile
+        qh, _ = quantize_raster(q, qt)
+        kh, _ = quantize_raster(k, qt)
+        vh, _ = quantize_raster(v, qt, per_channel=v_per_channel)
     else:
         qh, kh, vh = q, k, v
     toks = [(t, h, w) for t in range(T) for h in range(H) for w in range(W)]

@@ -208,6 +208,45 @@ def test_sparse_attention_matches_token_level_brute_force(window, fp8):
     assert np.max(np.abs(o - want)) <= 1e-12 * np.abs(want).max()
 
 
+def test_sub_tile_quantisation_groups_match_brute_force():
+    """Quantisation granularity finer than the sparsity tile (g and W as separate
+    hyper-parameters, Sec. 3.3): scales per sub-tile, window in whole tiles.  Pinned against the
+    token-level brute force, where the sub-tiles are simply the grid cut into sub-tile boxes; the
+    grid is ragged against the tile and against the sub-tile."""
+    g = fo.Geometry(3, 5, 7, 2, 4, 4, 1, 2, 4)              # tile (2,4,4) in 4 sub-tiles of (1,2,4)
+    assert g.NS == 4 and g.n_groups == g.M * 4
+    d = 8
+    q, k, v = rand_qkv(21, (g.T, g.H, g.W), d)
+    # group bookkeeping: every sub-tile box of the raster grid is one group
+    grp = fo.tile_unorder(fo.group_of_slot(g)[:, None].astype(np.float64), g)[..., 0]
+    for t in range(g.T):
+        for h in range(g.H):
+            for w in range(g.W):
+                same = grp == grp[t, h, w]
+                box = np.zeros_like(same)
+                box[t:t + 1, (h // 2) * 2:(h // 2) * 2 + 2, (w // 4) * 4:(w // 4) * 4 + 4] = True
+                assert np.array_equal(same, box)
+    # scales and codes against the brute force with the sub-tile as its quantisation box
+    codes, s = fo.quantize_tiles(fo.tile_order(q, g), g)
+    assert s.shape == (g.n_groups,)
+    deq = e4m3.decode(codes) * s.astype(np.float64)[fo.group_of_slot(g)][:, None]
+    want, _ = brute.quantize_raster(q, (1, 2, 4))
+    assert np.array_equal(fo.tile_unorder(deq, g), want)
+    coarse = fo.Geometry(3, 5, 7, 2, 4, 4)
+    assert not np.array_equal(fo.quantize_tiles(fo.tile_order(q, coarse), coarse)[0], codes)
+    for window in [(1, 3, 3), (3, 1, 1)]:
+        o = fo.attention(fo.tile_order(q, g), fo.tile_order(k, g), fo.tile_order(v, g), g, window)
+        want = brute.attention_raster(q, k, v, (2, 4, 4), window, True, qtile=(1, 2, 4))
+        assert np.max(np.abs(fo.tile_unorder(o, g) - want)) <= 1e-12 * np.abs(want).max()
+    # a sub-tile equal to the tile is the unified granularity, bit for bit
+    same = fo.Geometry(3, 5, 7, 2, 4, 4, 2, 4, 4)
+    a = fo.attention(fo.tile_order(q, same), fo.tile_order(k, same), fo.tile_order(v, same), same, (1, 3, 3))
+    b = fo.attention(fo.tile_order(q, coarse), fo.tile_order(k, coarse), fo.tile_order(v, coarse), coarse, (1, 3, 3))
+    assert np.array_equal(a, b)
+    with pytest.raises(AssertionError):
+        fo.Geometry(3, 5, 7, 2, 4, 4, 1, 3, 4)                # a sub-tile must divide the tile
+
+
 def test_channelwise_v_matches_brute_force():
     g = fo.Geometry(2, 3, 4, 1, 2, 2)
     d = 4
