@@ -30,6 +30,14 @@
  * zero in tiled inputs (fps_tile_order writes them so); padded keys never contribute to any
  * output and padded query rows are written as zero.
  *
+ * Quantisation sub-tiles (Sec. 3.3 treats the granularity g and the window W as separate
+ * hyper-parameters).  With (Qt,Qh,Qw) given, a tile is NS = (Tt/Qt)(Th/Qh)(Tw/Qw) sub-tiles of
+ * QS = Qt*Qh*Qw tokens, each rounded up to whole blocks (QSP slots, TSP = NS*QSP) and each with
+ * its own scale; in-tile order is then sub-tile-major: token (rt,rh,rw) of the tile sits in slot
+ * s*QSP + ((rt%Qt)*Qh + rh%Qh)*Qw + rw%Qw with s = ((rt/Qt)*(Th/Qh) + rh/Qh)*(Tw/Qw) + rw/Qw.
+ * Per-tile scale tensors become per-group tensors [B,heads,M*NS], group index u*NS + s
+ * (fps_num_groups = M*NS).
+ *
  * Supported now: head_dim = 128 and any tile of 1 <= TS <= 32768 tokens, e.g. (1,8,16), (3,4,4),
  * (6,8,8), (12,16,16), (24,32,32), so the granularity g(t) of Sec. 3.2 can change the tile shape
  * from one denoising regime to the next; anything else returns FPS_ERR_UNSUPPORTED.
@@ -70,6 +78,9 @@ typedef struct {
     int B, heads, head_dim;   /* head_dim must be 128                                             */
     int T, H, W;              /* real token grid                                                  */
     int Tt, Th, Tw;           /* tile; the padded grid is the grid rounded up to tile multiples   */
+    int Qt, Qh, Qw;           /* quantisation sub-tile: 0,0,0 = the tile itself (one scale per
+                                 tile); otherwise each must divide Tt, Th, Tw and every sub-tile
+                                 has its own scale while the window still counts whole tiles      */
 } fps_shape;
 
 typedef enum {
@@ -85,9 +96,10 @@ typedef enum {
  * whole axis (dense). */
 typedef struct { int wt, wh, ww; fps_edge edge; } fps_window;
 
-/* One regime of the schedule: precision, window W(t), and the tile granularity g(t) (Eq. 6).
- * Tt = Th = Tw = 0 means "whatever tile the shape of the call has". */
-typedef struct { fps_precision prec; fps_window win; int Tt, Th, Tw; } fps_regime;
+/* One regime of the schedule: precision, window W(t), and the granularity g(t) (Eq. 6) as a tile
+ * and, optionally, a quantisation sub-tile.  Tt = Th = Tw = 0 means "whatever tile the shape of
+ * the call has", Qt = Qh = Qw = 0 "whatever sub-tile it has". */
+typedef struct { fps_precision prec; fps_window win; int Tt, Th, Tw; int Qt, Qh, Qw; } fps_regime;
 
 /* Denoising-step-aware schedule (Eq. 6): step t in 1..num_steps, thresholds t1 = alpha1*num_steps,
  * t2 = alpha2*num_steps evaluated in float; regime[0] if t <= t1, regime[1] if t1 < t <= t2,
@@ -108,6 +120,9 @@ int fps_schedule_select(const fps_step_cfg* cfg, fps_regime* out);
 
 /* M, the number of tiles per head, or 0 on an invalid shape. */
 size_t fps_num_tiles(const fps_shape* shape);
+
+/* M*NS, the number of quantisation groups (scales) per head, or 0 on an invalid shape. */
+size_t fps_num_groups(const fps_shape* shape);
 
 /* TSP, the slots one tile occupies in tiled and packed tensors (TS rounded up to whole blocks),
  * or 0 on an invalid shape. */
@@ -137,7 +152,8 @@ int fps_tile_unorder(const fps_shape* shape, const void* o_tiled, fps_out_dtype 
 
 /* Eq. 4-5 (Algorithm 1 steps 2-3).  Tiled bf16 (device) -> E4M3 codes in the library's packed
  * operand layout for `role` (device, fps_packed_bytes(shape, FPS_PREC_FP8) bytes) and fp32 scales
- * (device): [B,heads,M] for per-tile scales, [B,heads,128] for FPS_VSCALE_CHANNEL (role V only).
+ * (device): [B,heads,M*NS] for per-group scales (one per tile, or per quantisation sub-tile),
+ * [B,heads,128] for FPS_VSCALE_CHANNEL (role V only).
  * scale = amax/448 as a correctly rounded float division (1.0 for an all-zero group); code =
  * round-to-nearest-even, saturating, of the exact quotient x/scale.  `vscale` is ignored for
  * roles Q and K. */
@@ -155,7 +171,7 @@ int fps_quantize_raster(const fps_shape* shape, const void* x_raster_bf16, fps_r
  * packed operand layout for `role` (device, fps_packed_bytes(shape, FPS_PREC_BF16) bytes).
  * Q and K keep their bf16 values.  V is stored as fp16 after an exact per-tile power-of-two
  * scaling (so that P can be held in fp16, 11 significant bits, in the PV product); the scales
- * 2^e go to vscale_out, fp32 [B,heads,M] (device), required for role V and ignored otherwise.
+ * 2^e go to vscale_out, fp32 [B,heads,M*NS] (device), required for role V and ignored otherwise.
  * bf16 values more than 2^28 times smaller than their tile's largest magnitude lose precision. */
 int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
                         void* xp_out, float* vscale_out, void* stream);
@@ -191,14 +207,15 @@ int fps_debug_scores_block_q8(const fps_shape* shape, const void* q, const void*
  *              (may be NULL) and sv is the vscale_out of fps_pack_tiles_bf16.
  *   step       if non-NULL, (prec, win) are replaced by fps_schedule_select(step); the packed
  *              tensors must match the selected precision, and if the selected regime names a
- *              tile it must be the tile of `shape` (the inputs were quantised with it), else
- *              FPS_ERR_INVALID_ARG.
+ *              tile or a sub-tile it must be that of `shape` (the inputs were quantised with
+ *              it), else FPS_ERR_INVALID_ARG.
  *   out        of dtype out_dt (device): tiled [B,heads,M*TSP,128] with padded query rows set to 0
  *              (FPS_LAYOUT_TILED), or raster [B,heads,T,H,W,128] holding the real tokens only
  *              (FPS_LAYOUT_RASTER: the inverse tile ordering is fused into the epilogue).
  *   visited    NULL, or device memory of M*M bytes zeroed by the caller: the kernel sets
  *              visited[u*M+v] = 1 for every tile pair it computes (written by head 0 only).
- * Scores are dequantised per tile pair (s^Q_u * s^K_v / sqrt(d)); softmax runs online in base 2
+ * Scores are dequantised per pair of quantisation groups (s^Q * s^K / sqrt(d); per tile pair
+ * without sub-tiles); softmax runs online in base 2
  * with an integer row reference; P is rounded to E4M3 after scaling by 448 (FP8) or to fp16
  * (BF16); the denominator sums the unrounded P. */
 int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision prec,

@@ -158,7 +158,9 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
             size_t row;
             if (a.out_raster) {
                 if (!valid) continue;
-                const int rw = rr % G.Tw, rh = (rr / G.Tw) % G.Th, rt = rr / (G.Tw * G.Th);
+                int rt = 0, rh = 0, rw = 0;
+                const int sub = rr / G.QSP;
+                sub_slot_coords(G, sub, rr - sub * G.QSP, &rt, &rh, &rw);
                 row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
             } else {
                 row = ((size_t)bh * G.M + u) * G.TSP + rr;
@@ -177,9 +179,10 @@ struct TileWalk {
     int t0, h0, w0, h1, w1;
     int vt, vh, vw;
     int jk, kb_cur;                         // block within the tile, blocks to visit in this tile
+    int js, jb, kbs;                        // jk = js * kbs + jb: sub-tile (scale group) and block in it
     int kb_full, kb_last, last_t;
     int n;                                  // number of key BLOCKS in the box
-    __device__ __forceinline__ void init(const AttnArgs& a, int KB, int KB_LAST, int ut, int uh, int uw) {
+    __device__ __forceinline__ void init(const AttnArgs& a, int KB, int KB_LAST, int KBS, int ut, int uh, int uw) {
         const Geom& G = a.g;
         if (a.edge_shift) {                 // clamp the centre into [r, n-1-r]; an axis not longer than
             // the window has no such centre and is kept whole by the truncation below with u = n/2
@@ -193,12 +196,13 @@ struct TileWalk {
         kb_full = KB; kb_last = KB_LAST; last_t = G.nT - 1;
         const int has_last = t1 == last_t;
         n = (h1 - h0 + 1) * (w1 - w0 + 1) * ((t1 - t0 + 1 - has_last) * KB + has_last * KB_LAST);
-        vt = t0; vh = h0; vw = w0; jk = 0;
+        vt = t0; vh = h0; vw = w0; jk = 0; js = 0; jb = 0; kbs = KBS;
         kb_cur = vt == last_t ? kb_last : kb_full;
     }
     __device__ __forceinline__ void next() {
+        if (++jb == kbs) { jb = 0; ++js; }
         if (++jk < kb_cur) return;
-        jk = 0;
+        jk = 0; js = 0; jb = 0;
         if (++vw > w1) {
             vw = w0;
             if (++vh > h1) { vh = h0; ++vt; kb_cur = vt == last_t ? kb_last : kb_full; }
@@ -217,14 +221,15 @@ __device__ __forceinline__ void zero_block_rows(const AttnArgs& a, int bh, int u
     for (int i = threadIdx.x; i < TS * (row_bytes / 16); i += NTHR) dst[i] = make_uint4(0, 0, 0, 0);
 }
 
-// Validity of the TS slots of block jk of a tile of class cls as wave-wide ballots: bit i of
-// word h says whether slot 64h + i of the block is a real token.  Evaluated arithmetically, so
-// that tiles of any size need no table.
+// Validity of the TS slots of block jb of sub-tile js of a tile of class cls as wave-wide ballots:
+// bit i of word h says whether slot 64h + i of the block is a real token.  Evaluated
+// arithmetically, so that tiles of any size need no table.
 template <int TS>
-__device__ __forceinline__ void block_ballots(const Geom& G, int cls, int jk, int lane,
+__device__ __forceinline__ void block_ballots(const Geom& G, int cls, int js, int jb, int lane,
                                               uint64_t (&bm)[(TS + 63) / 64]) {
 #pragma unroll
-    for (int h = 0; h < (TS + 63) / 64; ++h) bm[h] = __ballot(slot_is_token(G, cls, jk * TS + 64 * h + lane));
+    for (int h = 0; h < (TS + 63) / 64; ++h)
+        bm[h] = __ballot(sub_slot_is_token(G, cls, js, jb * TS + 64 * h + lane));
 }
 
 __device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
@@ -272,6 +277,8 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     const Geom& G = a.g;
     const int KB = MB ? G.KB : 1;                          // blocks per tile; 1 is a compile-time fact
     const int KB_LAST = MB ? G.kb_last : 1;                // ... of a last-along-T tile, without padding-only blocks
+    const int KBS = MB ? G.KBS : 1;                        // blocks per quantisation sub-tile (scale group)
+    const int NS = MB ? G.NS : 1;                          // sub-tiles per tile
     int bh, u, jq;
     if (!work_item(a, KB, &bh, &u, &jq)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
@@ -297,10 +304,10 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
     }
-    const float sqc = load_uniform(a.sq, tile0 + u) * kLog2eOverSqrtD;
+    const float sqc = load_uniform(a.sq, (tile0 + u) * NS + jq / KBS) * kLog2eOverSqrtD;
 
     TileWalk w0, w2;                                       // tile i, and the tile whose K is fetched (i+2)
-    w0.init(a, KB, KB_LAST, ut, uh, uw);
+    w0.init(a, KB, KB_LAST, KBS, ut, uh, uw);
     w2 = w0;
     const int ntiles = w0.n;
     auto tile_of = [&](const TileWalk& w) FPS_INLINE { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
@@ -368,7 +375,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
             asm volatile("" : "+v"(acc[qb][cb]));
         }
     };
-    auto mask_scores = [&](int cls, int jk) FPS_INLINE {              // padded keys of a boundary tile: -inf
+    auto mask_scores = [&](int cls, int js, int jb) FPS_INLINE {      // padded keys of a boundary tile: -inf
         cls = __builtin_amdgcn_readfirstlane(cls);         // wave-uniform by construction
         if (!((a.partial_cls >> cls) & 1u)) return;
         if (!MB) {
@@ -382,7 +389,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
                 }
         } else {                                           // block jk of a larger tile
             uint64_t bm[(TS + 63) / 64];
-            block_ballots<TS>(G, cls, jk, lane, bm);
+            block_ballots<TS>(G, cls, js, jb, lane, bm);
             bool all = true;
 #pragma unroll
             for (int h = 0; h < (TS + 63) / 64; ++h) all = all && (bm[h] | (TS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
@@ -413,11 +420,11 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < NB; ++b) qk_mfma(load_k(lds[0], b), b);
-    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
 
     float svv_prev = 0.f;
-    float sc_next = sqc * load_uniform(a.sk, tile0 + tile_of(w0));   // scales of the coming tile
-    float sv_next = VCH ? 1.f : load_uniform(a.sv, tile0 + tile_of(w0));
+    float sc_next = sqc * load_uniform(a.sk, (tile0 + tile_of(w0)) * NS + w0.js);   // scales of the coming block
+    float sv_next = VCH ? 1.f : load_uniform(a.sv, (tile0 + tile_of(w0)) * NS + w0.js);
     // One iteration.  FIRST: there is no previous tile whose PV is owed.  LAST: there is no next
     // tile whose scores can be started.  Both are compile-time so that the MFMA / VALU interleave
     // of the steady state carries no branches.
@@ -440,9 +447,9 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         if (fetch_k) w2.next();
         w0.next();
         if (!LAST) {                     // scales of tile i+1, needed next iteration
-            const int vn = tile_of(w0);
-            sc_next = sqc * load_uniform(a.sk, tile0 + vn);
-            if (!VCH) sv_next = load_uniform(a.sv, tile0 + vn);
+            const size_t gn = (tile0 + tile_of(w0)) * NS + w0.js;
+            sc_next = sqc * load_uniform(a.sk, gn);
+            if (!VCH) sv_next = load_uniform(a.sv, gn);
         }
 
         // ---- phase 1: row maxima of S(i)  |  delayed PV(i-1) --------------------------------
@@ -517,7 +524,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         }
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
-        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
         svv_prev = svv;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the staged tiles landed
     };
@@ -578,6 +585,8 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     const Geom& G = a.g;
     const int KB = MB ? G.KB : 1;                          // blocks per tile; 1 is a compile-time fact
     const int KB_LAST = MB ? G.kb_last : 1;                // ... of a last-along-T tile, without padding-only blocks
+    const int KBS = MB ? G.KBS : 1;                        // blocks per quantisation sub-tile (scale group)
+    const int NS = MB ? G.NS : 1;                          // sub-tiles per tile
     int bh, u, jq;
     if (!work_item(a, KB, &bh, &u, &jq)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
@@ -606,7 +615,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     const float sc = kLog2eOverSqrtD;
 
     TileWalk w0, w1;                                       // tile i and tile i+1
-    w0.init(a, KB, KB_LAST, ut, uh, uw);
+    w0.init(a, KB, KB_LAST, KBS, ut, uh, uw);
     w1 = w0;
     w1.next();
     const int ntiles = w0.n;
@@ -657,7 +666,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
             asm volatile("" : "+v"(acc[qb][cb]));
         }
     };
-    auto mask_scores = [&](int cls, int jk) FPS_INLINE {              // padded keys of a boundary tile: -inf
+    auto mask_scores = [&](int cls, int js, int jb) FPS_INLINE {      // padded keys of a boundary tile: -inf
         cls = __builtin_amdgcn_readfirstlane(cls);         // wave-uniform by construction
         if (!((a.partial_cls >> cls) & 1u)) return;
         if (!MB) {
@@ -671,7 +680,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
                 }
         } else {                                           // block jk of a larger tile
             uint64_t bm[(TS + 63) / 64];
-            block_ballots<TS>(G, cls, jk, lane, bm);
+            block_ballots<TS>(G, cls, js, jb, lane, bm);
             bool all = true;
 #pragma unroll
             for (int h = 0; h < (TS + 63) / 64; ++h) all = all && (bm[h] | (TS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
@@ -701,14 +710,14 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < NB; ++b) qk_block(b);
-    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
 
     float svv_prev = 0.f;
     auto iteration = [&](auto first_tag, auto last_tag) FPS_INLINE {
         constexpr bool FIRST = decltype(first_tag)::value;
         constexpr bool LAST = decltype(last_tag)::value;
         const int v = tile_of(w0);
-        const float svv = load_uniform(a.sv, tile0 + v);
+        const float svv = load_uniform(a.sv, (tile0 + v) * NS + w0.js);
         if (a.visited && bh == 0 && tid == 0 && jq == 0 && w0.jk == 0) a.visited[(size_t)u * G.M + v] = 1;
         const uint8_t* ksrc = LAST ? nullptr : k_blk(w1);
         const uint8_t* vsrc = v_blk(w0);
@@ -787,7 +796,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
         for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
         w0.next();
         w1.next();
-        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.jk);
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
         svv_prev = svv;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // V(i): this thread's share landed
     };

@@ -4,38 +4,41 @@
 
 namespace fps {
 
-// Where a block of BS slots sits: its head, the grid origin of its tile and its first slot.
-// Computed once per workgroup (the divisions are by run-time values).
+// Where a block of BS slots sits: its head, the grid origin of its SUB-TILE and its first slot
+// within the sub-tile.  Computed once per workgroup (the divisions are by run-time values).
 struct BlockOrigin {
     long long bh;
-    int t0, h0, w0;      // grid coordinates of the tile's first token
-    int slot0;           // first in-tile slot of the block
+    int t0, h0, w0;      // grid coordinates of the sub-tile's first token
+    int slot0;           // first in-sub-tile slot of the block
 };
 __device__ __forceinline__ BlockOrigin block_origin(const Geom& g, int blk) {
     BlockOrigin o;
-    const int tile_lin = blk / g.KB;                     // 32-bit: the block count fits a grid dimension
-    o.slot0 = (blk - tile_lin * g.KB) * g.BS;
+    const int group = blk / g.KBS;                       // 32-bit: the block count fits a grid dimension
+    o.slot0 = (blk - group * g.KBS) * g.BS;
+    const int tile_lin = group / g.NS, s = group - tile_lin * g.NS;
     const int bh = tile_lin / g.M;
     const int u = tile_lin - bh * g.M;
     const int ut = u / (g.nW * g.nH), rem = u - ut * (g.nW * g.nH);
     const int uh = rem / g.nW, uw = rem - uh * g.nW;
+    const int st = s / (g.nsH * g.nsW), srem = s - st * (g.nsH * g.nsW);
+    const int sh = srem / g.nsW, sw = srem - sh * g.nsW;
     o.bh = bh;
-    o.t0 = ut * g.Tt; o.h0 = uh * g.Th; o.w0 = uw * g.Tw;
+    o.t0 = ut * g.Tt + st * g.Qt; o.h0 = uh * g.Th + sh * g.Qh; o.w0 = uw * g.Tw + sw * g.Qw;
     return o;
 }
 
 // The 16 uint4 (256 bytes) of the bf16 row of the token in slot r of block `blk`.  TILED input:
-// blocks are contiguous.  RASTER input: the token's (t,h,w) is recovered from the tile origin and
-// the in-tile slot; padding slots return nullptr.
+// blocks are contiguous.  RASTER input: the token's (t,h,w) is recovered from the sub-tile origin
+// and the in-sub-tile slot; padding slots return nullptr.
 template <bool RASTER>
 __device__ __forceinline__ const uint4* token_row(const uint4* x, const Geom& g, const BlockOrigin& o,
                                                   int blk, int r) {
     if (!RASTER) return x + ((long long)blk * g.BS + r) * 16;
     const int slot = o.slot0 + r;
-    if (slot >= g.TS) return nullptr;                    // slots past the tile's tokens are padding
-    const int plane = g.Th * g.Tw;
+    if (slot >= g.QS) return nullptr;                    // slots past the sub-tile's tokens are padding
+    const int plane = g.Qh * g.Qw;
     const int rt = slot / plane, rem = slot - rt * plane;
-    const int rh = rem / g.Tw, rw = rem - rh * g.Tw;
+    const int rh = rem / g.Qw, rw = rem - rh * g.Qw;
     const int t = o.t0 + rt, h = o.h0 + rh, w = o.w0 + rw;
     if (t >= g.T || h >= g.H || w >= g.W) return nullptr;
     return x + ((((o.bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);
@@ -87,8 +90,8 @@ static __global__ void amax_to_pow2_kernel(float* p, int n) {        // amax -> 
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = __uint_as_float((uint32_t)(127 + pow2_exponent_for_fp16(p[i])) << 23);
 }
-// tile amax over the KB blocks of each tile: one workgroup per block, merged with an atomic max on
-// the float bit pattern (amax_bits must be cleared first)
+// amax over the KBS blocks of each quantisation group: one workgroup per block, merged with an
+// atomic max on the float bit pattern (amax_bits must be cleared first)
 template <bool RASTER>
 __global__ __launch_bounds__(256) void block_amax_kernel(const uint4* __restrict__ x,
                                                          uint32_t* __restrict__ amax_bits, Geom g) {
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(256) void block_amax_kernel(const uint4* __restrict
         if (row) m = amax_bits16(row[c & 15], m);
     }
     m = block_max_256(m, red);
-    if (threadIdx.x == 0) atomicMax(&amax_bits[blockIdx.x / g.KB], m << 16);
+    if (threadIdx.x == 0) atomicMax(&amax_bits[blockIdx.x / g.KBS], m << 16);
 }
 
 }  // namespace fps

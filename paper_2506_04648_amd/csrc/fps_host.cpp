@@ -51,9 +51,23 @@ int check_shape(const fps_shape* s, Geom* g) {
         set_error("tile of %lld tokens unsupported (at most %d)", ts, kMaxTileTokens);
         return FPS_ERR_UNSUPPORTED;
     }
-    // 32-token blocks when they waste fewer slots than 128-token blocks (TS <= 96)
-    const int bs = (ts <= 128 && (ts + 31) / 32 * 32 < 128) ? 32 : 128;
-    const int kb = (int)((ts + bs - 1) / bs);
+    int qt = s->Qt, qh = s->Qh, qw = s->Qw;
+    if (qt == 0 && qh == 0 && qw == 0) { qt = s->Tt; qh = s->Th; qw = s->Tw; }
+    if (qt <= 0 || qh <= 0 || qw <= 0 || s->Tt % qt || s->Th % qh || s->Tw % qw) {
+        set_error("quantisation sub-tile (%d,%d,%d) must be all zero or divide the tile (%d,%d,%d)",
+                  s->Qt, s->Qh, s->Qw, s->Tt, s->Th, s->Tw);
+        return FPS_ERR_INVALID_ARG;
+    }
+    const int qs = qt * qh * qw;
+    const int ns = (s->Tt / qt) * (s->Th / qh) * (s->Tw / qw);
+    // 32-slot blocks when they waste fewer slots than 128-slot blocks (sub-tiles of <= 96 tokens)
+    const int bs = (qs <= 128 && (qs + 31) / 32 * 32 < 128) ? 32 : 128;
+    const int kbs = (qs + bs - 1) / bs;
+    const long long kb = (long long)ns * kbs;
+    if (kb * bs > 4LL * kMaxTileTokens) {
+        set_error("tile of %lld slots after padding its %d sub-tiles to whole blocks is too large", kb * bs, ns);
+        return FPS_ERR_UNSUPPORTED;
+    }
     if (bh > (1 << 20) || m > (1 << 20) || bh * m * kb >= (1LL << 30)) {
         set_error("shape too large (B*heads*M*blocks-per-tile must stay below 2^30)");
         return FPS_ERR_INVALID_ARG;
@@ -64,11 +78,20 @@ int check_shape(const fps_shape* s, Geom* g) {
     g->Tt = s->Tt; g->Th = s->Th; g->Tw = s->Tw;
     g->nT = nT; g->nH = nH; g->nW = nW;
     g->M = (int)m; g->TS = (int)ts;
-    g->BS = bs; g->KB = kb; g->TSP = kb * bs;
+    g->Qt = qt; g->Qh = qh; g->Qw = qw;
+    g->nsT = s->Tt / qt; g->nsH = s->Th / qh; g->nsW = s->Tw / qw;
+    g->NS = ns; g->QS = qs;
+    g->BS = bs; g->KBS = kbs; g->QSP = kbs * bs; g->KB = (int)kb; g->TSP = (int)kb * bs;
     g->lastT = s->T - (nT - 1) * s->Tt;
     g->lastH = s->H - (nH - 1) * s->Th;
     g->lastW = s->W - (nW - 1) * s->Tw;
-    g->kb_last = (g->lastT * s->Th * s->Tw + bs - 1) / bs;
+    // sub-tile layers along t that hold a real plane of a last-along-T tile; within the last such
+    // layer the padding-only blocks form a suffix only if the layer is a single sub-tile
+    const int layers = (g->lastT + qt - 1) / qt;
+    if (g->nsH * g->nsW == 1)
+        g->kb_last = (layers - 1) * kbs + ((g->lastT - (layers - 1) * qt) * qh * qw + bs - 1) / bs;
+    else
+        g->kb_last = layers * g->nsH * g->nsW * kbs;
     return FPS_OK;
 }
 
@@ -119,6 +142,11 @@ int fps_schedule_select(const fps_step_cfg* cfg, fps_regime* out) {
             set_error("regime %d: tile (%d,%d,%d) must be all zero or all positive", i, r.Tt, r.Th, r.Tw);
             return FPS_ERR_INVALID_ARG;
         }
+        const bool qnone = r.Qt == 0 && r.Qh == 0 && r.Qw == 0;
+        if (!qnone && (r.Qt <= 0 || r.Qh <= 0 || r.Qw <= 0)) {
+            set_error("regime %d: sub-tile (%d,%d,%d) must be all zero or all positive", i, r.Qt, r.Qh, r.Qw);
+            return FPS_ERR_INVALID_ARG;
+        }
     }
     const float t1 = cfg->alpha1 * (float)cfg->num_steps;
     const float t2 = cfg->alpha2 * (float)cfg->num_steps;
@@ -131,6 +159,12 @@ size_t fps_num_tiles(const fps_shape* shape) {
     Geom g;
     if (check_shape(shape, &g) != FPS_OK) return 0;
     return (size_t)g.M;
+}
+
+size_t fps_num_groups(const fps_shape* shape) {
+    Geom g;
+    if (check_shape(shape, &g) != FPS_OK) return 0;
+    return (size_t)g.M * g.NS;
 }
 
 size_t fps_tile_slots(const fps_shape* shape) {
@@ -309,12 +343,18 @@ int fps_attn_fwd(const fps_shape* shape, const fps_window* win, fps_precision pr
                       step->step, sel.Tt, sel.Th, sel.Tw, shape->Tt, shape->Th, shape->Tw);
             return FPS_ERR_INVALID_ARG;
         }
+        if (sel.Qt != 0 && (sel.Qt != g.Qt || sel.Qh != g.Qh || sel.Qw != g.Qw)) {
+            set_error("step %d selects sub-tile (%d,%d,%d) but the shape of the call has (%d,%d,%d)",
+                      step->step, sel.Qt, sel.Qh, sel.Qw, g.Qt, g.Qh, g.Qw);
+            return FPS_ERR_INVALID_ARG;
+        }
     } else {
         FPS_TRY(check_window(win));
         FPS_TRY(check_enum(prec, FPS_PREC_FP8, "prec"));
         sel.prec = prec;
         sel.win = *win;
         sel.Tt = sel.Th = sel.Tw = 0;
+        sel.Qt = sel.Qh = sel.Qw = 0;
     }
     FPS_TRY(check_enum(vscale, FPS_VSCALE_CHANNEL, "vscale"));
     FPS_TRY(check_enum(out_dt, FPS_OUT_F32, "out_dt"));

@@ -18,26 +18,49 @@ struct Geom {
     int Tt, Th, Tw;
     int nT, nH, nW;
     int M, TS;
-    // The kernels work on blocks of BS tokens (128 or 32); a tile occupies KB = ceil(TS/BS)
-    // consecutive blocks, TSP = KB*BS slots, and has ONE scale.  Block index = tile * KB + block
-    // in tile.  Slot r of a tile holds the token of in-tile rank r if r < TS, else padding.
-    int BS, KB, TSP;
+    // Quantisation sub-tile (Qt,Qh,Qw) (= the tile when none is given): a tile is NS = nsT*nsH*nsW
+    // sub-tiles of QS tokens, each with its own scale; sub-tile s = (st*nsH + sh)*nsW + sw.
+    int Qt, Qh, Qw;
+    int nsT, nsH, nsW, NS, QS;
+    // The kernels work on blocks of BS slots (128 or 32).  A sub-tile occupies KBS = ceil(QS/BS)
+    // consecutive blocks (QSP = KBS*BS slots, slot rr < QS holding the token of in-sub-tile rank
+    // rr, the rest padding), a tile KB = NS*KBS blocks (TSP = KB*BS slots).  Block index =
+    // tile * KB + block in tile; scale (group) index = tile * NS + sub-tile = block index / KBS.
+    int BS, KBS, QSP, KB, TSP;
     // Real planes / rows / columns of the LAST tile along each axis (all others are full).  A
     // tile's boundary class is c = 4*(last along T) + 2*(last along H) + (last along W).
     int lastT, lastH, lastW;
-    // Blocks of a last-along-T tile that hold at least one real token: its slots from
-    // lastT*Th*Tw on are all padding, so those blocks are never computed.
+    // Leading blocks of a last-along-T tile that can hold a real token: the blocks after them
+    // are padding only and are never computed.
     int kb_last;
 };
 
-// slot r of a tile of boundary class c holds a real token
-__host__ __device__ inline bool slot_is_token(const Geom& g, int c, int r) {
-    if (r >= g.TS) return false;
-    const int plane = g.Th * g.Tw;
-    const int rt = r / plane, rem = r - rt * plane;
-    const int rh = rem / g.Tw, rw = rem - rh * g.Tw;
+// In-tile coordinates (rt, rh, rw) of slot rr of sub-tile s; false if the slot is padding of the
+// sub-tile (rr >= QS).
+__host__ __device__ inline bool sub_slot_coords(const Geom& g, int s, int rr, int* rt, int* rh, int* rw) {
+    if (rr >= g.QS) return false;
+    const int layer = g.nsH * g.nsW;
+    const int st = s / layer, srem = s - st * layer;
+    const int sh = srem / g.nsW, sw = srem - sh * g.nsW;
+    const int plane = g.Qh * g.Qw;
+    const int a = rr / plane, rem = rr - a * plane;
+    const int b = rem / g.Qw, c = rem - b * g.Qw;
+    *rt = st * g.Qt + a; *rh = sh * g.Qh + b; *rw = sw * g.Qw + c;
+    return true;
+}
+
+// slot rr of sub-tile s of a tile of boundary class c holds a real token
+__host__ __device__ inline bool sub_slot_is_token(const Geom& g, int c, int s, int rr) {
+    int rt, rh, rw;
+    if (!sub_slot_coords(g, s, rr, &rt, &rh, &rw)) return false;
     return rt < ((c & 4) ? g.lastT : g.Tt) && rh < ((c & 2) ? g.lastH : g.Th) &&
            rw < ((c & 1) ? g.lastW : g.Tw);
+}
+
+// slot r (0 .. TSP-1) of a tile of boundary class c holds a real token
+__host__ __device__ inline bool slot_is_token(const Geom& g, int c, int r) {
+    const int s = r / g.QSP;
+    return sub_slot_is_token(g, c, s, r - s * g.QSP);
 }
 
 void set_error(const char* fmt, ...);

@@ -33,10 +33,12 @@ __global__ void tile_order_kernel(const uint4* __restrict__ in, uint4* __restric
     const int u = (int)(bu % g.M);
     const long long bh = bu / g.M;
     const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
-    const int rw = r % g.Tw, rh = (r / g.Tw) % g.Th, rt = r / (g.Tw * g.Th);
+    const int s = r / g.QSP;
+    int rt = 0, rh = 0, rw = 0;
+    const bool slot_used = sub_slot_coords(g, s, r - s * g.QSP, &rt, &rh, &rw);
     const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (r < g.TS && t < g.T && h < g.H && w < g.W) {
+    if (slot_used && t < g.T && h < g.H && w < g.W) {
         const long long src = (((bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16 + c16;
         val = in[src];
     }
@@ -55,7 +57,9 @@ __global__ void tile_unorder_kernel(const uint4* __restrict__ in, uint4* __restr
     const int t = (int)(tok % g.T);
     const long long bh = tok / g.T;
     const int u = ((t / g.Tt) * g.nH + h / g.Th) * g.nW + w / g.Tw;
-    const int r = ((t % g.Tt) * g.Th + h % g.Th) * g.Tw + w % g.Tw;
+    const int rt = t % g.Tt, rh = h % g.Th, rw = w % g.Tw;
+    const int s = ((rt / g.Qt) * g.nsH + rh / g.Qh) * g.nsW + rw / g.Qw;
+    const int r = s * g.QSP + ((rt % g.Qt) * g.Qh + rh % g.Qh) * g.Qw + rw % g.Qw;
     const long long src = ((bh * g.M + u) * (long long)g.TSP + r) * chunks_per_row + c;
     out[i] = in[src];
 }
@@ -99,7 +103,7 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
     }
     float amax;
     if (tile_amax) {
-        amax = tile_amax[blk / g.KB];
+        amax = tile_amax[blk / g.KBS];
         __syncthreads();
     } else {
         mb = block_max_256(mb, red);                       // also orders the LDS writes above
@@ -177,9 +181,9 @@ int launch_copy(const void* in, void* out, long long bytes, hipStream_t st) {
 }
 
 int launch_pack_bf16(const Geom& g, const void* x, int role, void* xp, float* vscale, hipStream_t st) {
-    const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M;
+    const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M * g.NS;   // ntiles: quantisation groups
     const float* tile_amax = nullptr;
-    if (role == FPS_ROLE_V && g.KB > 1) {                  // `vscale` holds the tile amax meanwhile
+    if (role == FPS_ROLE_V && g.KBS > 1) {                  // `vscale` holds the tile amax meanwhile
         clear_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>((uint32_t*)vscale, ntiles);
         block_amax_kernel<false><<<blocks, 256, 0, st>>>((const uint4*)x, (uint32_t*)vscale, g);
         tile_amax = vscale;

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __rest
     }
     float amax;
     if (tile_amax) {
-        amax = tile_amax[blk / g.KB];
+        amax = tile_amax[blk / g.KBS];
     } else {
         mb = block_max_256(mb, red);
         amax = __uint_as_float(mb << 16);
@@ -247,11 +247,11 @@ static int launch_quantize_channels(const Geom& g, const void* x, int raster, vo
 int launch_quantize(const Geom& g, const void* x, int raster, int role, int vscale, void* xq,
                     float* scales, hipStream_t st) {
     if (vscale != FPS_VSCALE_TILE) return launch_quantize_channels(g, x, raster, xq, scales, st);
-    const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M;
+    const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M * g.NS;   // ntiles: quantisation groups
     const uint4* xi = (const uint4*)x;
     uint8_t* xo = (uint8_t*)xq;
     const float* tile_amax = nullptr;
-    if (g.KB > 1) {                     // tile amax over several blocks first; `scales` holds it meanwhile
+    if (g.KBS > 1) {                     // tile amax over several blocks first; `scales` holds it meanwhile
         clear_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>((uint32_t*)scales, ntiles);
         if (raster) block_amax_kernel<true><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
         else        block_amax_kernel<false><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
@@ -264,7 +264,7 @@ int launch_quantize(const Geom& g, const void* x, int raster, int role, int vsca
         if (raster) quantize_tiles_kernel<32, true><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
         else        quantize_tiles_kernel<32, false><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
     }
-    if (g.KB > 1) amax_to_scale_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>(scales, ntiles);
+    if (g.KBS > 1) amax_to_scale_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>(scales, ntiles);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "quantize_tiles launch");
 }

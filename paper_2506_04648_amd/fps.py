@@ -24,7 +24,8 @@ OUT_BF16, OUT_F32 = 0, 1
 LAYOUT_TILED, LAYOUT_RASTER = 0, 1
 EDGE_TRUNCATE, EDGE_SHIFT = 0, 1
 
-EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_tile_slots", "fps_packed_bytes",
+EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_num_groups", "fps_tile_slots",
+           "fps_packed_bytes",
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
            "fps_quantize_raster",
            "fps_pack_tiles_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
@@ -33,7 +34,8 @@ EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_tile_s
 
 
 class Shape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("B", "heads", "head_dim", "T", "H", "W", "Tt", "Th", "Tw")]
+    _fields_ = [(n, ctypes.c_int) for n in ("B", "heads", "head_dim", "T", "H", "W", "Tt", "Th", "Tw",
+                                            "Qt", "Qh", "Qw")]
 
 
 class Window(ctypes.Structure):
@@ -41,8 +43,8 @@ class Window(ctypes.Structure):
 
 
 class Regime(ctypes.Structure):
-    _fields_ = [("prec", ctypes.c_int), ("win", Window), ("Tt", ctypes.c_int), ("Th", ctypes.c_int),
-                ("Tw", ctypes.c_int)]
+    _fields_ = [("prec", ctypes.c_int), ("win", Window)] + [(n, ctypes.c_int) for n in
+                                                            ("Tt", "Th", "Tw", "Qt", "Qh", "Qw")]
 
 
 class StepCfg(ctypes.Structure):
@@ -73,6 +75,8 @@ def lib():
         L.fps_schedule_select.argtypes = [ctypes.POINTER(StepCfg), ctypes.POINTER(Regime)]
         L.fps_num_tiles.restype = ctypes.c_size_t
         L.fps_num_tiles.argtypes = [ctypes.POINTER(Shape)]
+        L.fps_num_groups.restype = ctypes.c_size_t
+        L.fps_num_groups.argtypes = [ctypes.POINTER(Shape)]
         L.fps_tile_slots.restype = ctypes.c_size_t
         L.fps_tile_slots.argtypes = [ctypes.POINTER(Shape)]
         L.fps_packed_bytes.restype = ctypes.c_size_t
@@ -92,7 +96,8 @@ def lib():
         L.fps_attn_fwd.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), ip,
                                    ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, ip, vp, vp]
         for name in EXPORTS:
-            if name not in ("fps_last_error", "fps_num_tiles", "fps_tile_slots", "fps_packed_bytes"):
+            if name not in ("fps_last_error", "fps_num_tiles", "fps_num_groups", "fps_tile_slots",
+                            "fps_packed_bytes"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -107,13 +112,16 @@ def _check(status):
         raise FpsError(status, last_error())
 
 
-def make_shape(heads, grid, tile, B=1, head_dim=128) -> Shape:
-    return Shape(B, heads, head_dim, grid[0], grid[1], grid[2], tile[0], tile[1], tile[2])
+def make_shape(heads, grid, tile, B=1, head_dim=128, qtile=None) -> Shape:
+    """qtile: quantisation sub-tile (it must divide the tile); None = one scale per tile."""
+    q = (0, 0, 0) if qtile is None else tuple(qtile)
+    return Shape(B, heads, head_dim, grid[0], grid[1], grid[2], tile[0], tile[1], tile[2], q[0], q[1], q[2])
 
 
 def make_step_cfg(step, num_steps, alpha1, alpha2, regimes) -> StepCfg:
-    """regimes: three (prec, (wt, wh, ww[, edge])[, (Tt, Th, Tw)]) entries for the early, mid and
-    late steps (Eq. 6); the optional third item is the regime's tile granularity g(t)."""
+    """regimes: three (prec, (wt, wh, ww[, edge])[, (Tt, Th, Tw)[, (Qt, Qh, Qw)]]) entries for the
+    early, mid and late steps (Eq. 6); the optional items are the regime's granularity g(t): its
+    tile and its quantisation sub-tile."""
     cfg = StepCfg()
     cfg.step, cfg.num_steps, cfg.alpha1, cfg.alpha2 = step, num_steps, alpha1, alpha2
     for i, reg in enumerate(regimes):
@@ -121,6 +129,8 @@ def make_step_cfg(step, num_steps, alpha1, alpha2, regimes) -> StepCfg:
         cfg.regime[i].win = Window(*reg[1])
         if len(reg) > 2 and reg[2] is not None:
             cfg.regime[i].Tt, cfg.regime[i].Th, cfg.regime[i].Tw = reg[2]
+        if len(reg) > 3 and reg[3] is not None:
+            cfg.regime[i].Qt, cfg.regime[i].Qh, cfg.regime[i].Qw = reg[3]
     return cfg
 
 
@@ -135,17 +145,26 @@ def _ptr(t):
 
 # ---- host helpers ---------------------------------------------------------------------------
 def schedule_select(cfg: StepCfg, with_tile=False):
-    """(prec, window) of the step's regime; with_tile=True appends its tile (Tt, Th, Tw) or None."""
+    """(prec, window) of the step's regime; with_tile=True appends its tile (Tt, Th, Tw) or None,
+    and its quantisation sub-tile if it names one."""
     out = Regime()
     _check(lib().fps_schedule_select(ctypes.byref(cfg), ctypes.byref(out)))
     win = (out.win.wt, out.win.wh, out.win.ww) + ((out.win.edge,) if out.win.edge else ())
     if with_tile:
-        return out.prec, win, ((out.Tt, out.Th, out.Tw) if out.Tt else None)
+        tile = (out.Tt, out.Th, out.Tw) if out.Tt else None
+        if out.Qt:
+            return out.prec, win, tile, (out.Qt, out.Qh, out.Qw)
+        return out.prec, win, tile
     return out.prec, win
 
 
 def num_tiles(shape: Shape) -> int:
     return int(lib().fps_num_tiles(ctypes.byref(shape)))
+
+
+def num_groups(shape: Shape) -> int:
+    """Quantisation groups (scales) per head: one per tile, or per sub-tile of each tile."""
+    return int(lib().fps_num_groups(ctypes.byref(shape)))
 
 
 def tile_slots(shape: Shape) -> int:
@@ -208,7 +227,7 @@ def quantize_tiles(shape: Shape, x_tiled, role, vscale=VSCALE_TILE, out=None, sc
     if out is None:
         out = torch.empty(packed_bytes(shape, PREC_FP8), dtype=torch.uint8, device=x_tiled.device)
     if scales is None:
-        n = shape.head_dim if (role == ROLE_V and vscale == VSCALE_CHANNEL) else num_tiles(shape)
+        n = shape.head_dim if (role == ROLE_V and vscale == VSCALE_CHANNEL) else num_groups(shape)
         scales = torch.empty((shape.B, shape.heads, n), dtype=torch.float32, device=x_tiled.device)
     fn = lib().fps_quantize_raster if raster else lib().fps_quantize_tiles
     _check(fn(ctypes.byref(shape), _ptr(x_tiled), role, vscale, _ptr(out), _ptr(scales), _stream()))
@@ -222,7 +241,7 @@ def pack_tiles_bf16(shape: Shape, x_tiled, role, out=None, vscale=None):
     if out is None:
         out = torch.empty(packed_bytes(shape, PREC_BF16), dtype=torch.uint8, device=x_tiled.device)
     if role == ROLE_V and vscale is None:
-        vscale = torch.empty((shape.B, shape.heads, num_tiles(shape)), dtype=torch.float32,
+        vscale = torch.empty((shape.B, shape.heads, num_groups(shape)), dtype=torch.float32,
                              device=x_tiled.device)
     _check(lib().fps_pack_tiles_bf16(ctypes.byref(shape), _ptr(x_tiled), role, _ptr(out),
                                      _ptr(vscale), _stream()))

@@ -21,8 +21,8 @@ TAU = 2.0 ** -18
 ACC_EPS = 2.0 ** -12
 
 
-def geometry(w: synth.Workload) -> fo.Geometry:
-    return fo.Geometry(*w.grid, *w.tile)
+def geometry(w: synth.Workload, qtile=None) -> fo.Geometry:
+    return fo.Geometry(*w.grid, *w.tile, *(qtile or (0, 0, 0)))
 
 
 def to_device_bf16(x_np):
@@ -33,22 +33,31 @@ def to_device_bf16(x_np):
 class GpuRun:
     """Inputs of a workload on the GPU, tile-ordered and packed by the library's own kernels."""
 
-    def __init__(self, w: synth.Workload, qkv=None, call_index=0, heads=None):
+    def __init__(self, w: synth.Workload, qkv=None, call_index=0, heads=None, qtile=None):
         import torch
         self.w = w
         self.heads = list(range(w.heads)) if heads is None else list(heads)
-        self.shape = fps.make_shape(len(self.heads), w.grid, w.tile)
-        self.g = geometry(w)
+        self.shape = fps.make_shape(len(self.heads), w.grid, w.tile, qtile=qtile)
+        self.g = geometry(w, qtile)
         self.qkv = synth.qkv_raster(w, call_index, self.heads) if qkv is None else qkv
         self.raster = [to_device_bf16(a[None]) for a in self.qkv]
         self.tiled = [fps.tile_order(self.shape, r) for r in self.raster]
         self.torch = torch
-        # The library's tiled tensors give every tile TSP >= TS slots (whole blocks); the oracle's
-        # tile order has exactly TS rows per tile.  slots[i] = library slot of oracle row i.
+        # The library's tiled tensors give every tile TSP >= TS slots: each quantisation sub-tile
+        # (the whole tile unless a finer one is given) is rounded up to whole blocks and the
+        # sub-tiles of a tile follow each other.  The oracle's tile order has exactly TS rows per
+        # tile in (rt, rh, rw) order.  slots[i] = library slot of oracle row i.
         self.tsp = fps.tile_slots(self.shape)
         g = self.g
         assert self.tsp >= g.TS and fps.num_tiles(self.shape) == g.M
-        self.slots = (np.arange(g.M)[:, None] * self.tsp + np.arange(g.TS)[None, :]).reshape(-1)
+        assert fps.num_groups(self.shape) == g.n_groups and self.tsp % g.NS == 0
+        qt, qh, qw = g.qtile
+        r = np.arange(g.TS)
+        rw, rh, rt = r % g.Tw, (r // g.Tw) % g.Th, r // (g.Tw * g.Th)
+        sub = ((rt // qt) * (g.Th // qh) + rh // qh) * (g.Tw // qw) + rw // qw
+        rank_in_sub = ((rt % qt) * qh + rh % qh) * qw + rw % qw
+        in_tile = sub * (self.tsp // g.NS) + rank_in_sub
+        self.slots = (np.arange(g.M)[:, None] * self.tsp + in_tile[None, :]).reshape(-1)
 
     def pad_slots(self):
         """Boolean mask over the M*TSP library slots: True where the slot holds no real token."""
@@ -105,9 +114,11 @@ def gpu_raw_scores(run: GpuRun, head_slot, part):
                              for v in tiles], dim=1)
         run.torch.cuda.synchronize()
         raw = raw.cpu().numpy()
-        local = np.searchsorted(tiles, part["cols"] // g.TS) * run.tsp + part["cols"] % g.TS
-        return raw[:g.TS, local]
+        in_tile = run.slots[:g.TS]                                   # oracle in-tile rank -> library slot
+        local = np.searchsorted(tiles, part["cols"] // g.TS) * run.tsp + in_tile[part["cols"] % g.TS]
+        return raw[in_tile][:, local]
     bs = 128
+    assert g.NS == 1
     raw = np.zeros((g.TS, part["cols"].size), dtype=np.float32)
     q_slots = np.flatnonzero(part["rows_valid"])                     # in-tile slots of real query rows
     k_tile, k_slot = part["cols"] // g.TS, part["cols"] % g.TS
@@ -128,21 +139,22 @@ def fp8_tie_slack(run: GpuRun, head_slot, part, ref_rows):
     takes the softmax of ITS score accumulators (exact products, hardware accumulation, whose
     error is bounded separately by score_error_ratio) while the oracle takes it of the exact dot
     products.  The kernel's decisions are re-enacted in float32 from the raw scores it reports.
-    Two terms: (a) the E4M3 codes of P -- elements whose code differs, elements within TAU of a
+    Three terms: (a) the E4M3 codes of P -- elements whose code differs, elements within TAU of a
     rounding boundary, and elements in the subnormal range of the format; (b) the row sum l of
     the unquantised weights, which scales the whole row (it matters only for rows whose scores
     are large, where a relative score error of 2^-13 is an absolute error of 1e-2 in S')."""
     g = run.g
     (_, sq), (_, sk), _ = run.q8
     raw = gpu_raw_scores(run, head_slot, part)                          # float32
-    sq32 = sq[0, head_slot, part["u"]].cpu().numpy().astype(np.float32)
-    sk32 = sk[0, head_slot].cpu().numpy().astype(np.float32)[part["cols"] // g.TS]
+    grp = fo.group_of_slot(g)                                           # scale group of every oracle row
+    sq32 = sq[0, head_slot].cpu().numpy().astype(np.float32)[grp[part["u"] * g.TS:(part["u"] + 1) * g.TS]]
+    sk32 = sk[0, head_slot].cpu().numpy().astype(np.float32)[grp[part["cols"]]]
     c32 = np.float32(fo.LOG2E / np.sqrt(128.0))
-    sc32 = (sq32 * c32) * sk32                                          # same order as the kernel
-    m_gpu = np.ceil((raw * sc32[None, :]).max(axis=1)).astype(np.float64)
+    sc32 = (sq32 * c32)[:, None] * sk32[None, :]                        # same order as the kernel
+    m_gpu = np.ceil((raw * sc32).max(axis=1)).astype(np.float64)
     # the kernel carries the factor 448 in the exponent: 2^(fma(raw, sc, log2(448) - m))
     cm = (np.float32(np.log2(448.0)) - m_gpu.astype(np.float32)).astype(np.float64)
-    x = (raw.astype(np.float64) * sc32.astype(np.float64)[None, :] + cm[:, None]).astype(np.float32)
+    x = (raw.astype(np.float64) * sc32.astype(np.float64) + cm[:, None]).astype(np.float32)
     y_gpu = np.exp2(x.astype(np.float64))
     ph_gpu = e4m3.round_to_e4m3(y_gpu) / e4m3.FP8_MAX * np.exp2(m_gpu - part["m"])[:, None]
     d_elem = np.abs(ph_gpu - part["ph"]) + e4m3.rounding_slack(e4m3.FP8_MAX * part["p"], TAU) / e4m3.FP8_MAX
@@ -150,6 +162,11 @@ def fp8_tie_slack(run: GpuRun, head_slot, part, ref_rows):
     l_min = np.minimum(l_gpu, part["l"])
     slack = (d_elem @ np.abs(part["v"])) / l_min[:, None]
     slack += np.abs(ref_rows) * (np.abs(l_gpu - part["l"]) / l_min)[:, None]
+    # (c) the PV product runs on the same matrix instruction, whose accumulation error is bounded
+    # by ACC_EPS of the sum of absolute products (asserted on the scores by
+    # test_score_accumulation_error_model); it matters where sum_j P_j |v_j| is far above the
+    # output RMS (dense windows over outlier channels)
+    slack += ACC_EPS * (part["ph"] @ np.abs(part["v"])) / l_min[:, None]
     slack[~part["rows_valid"]] = 0.0
     flips = int(np.count_nonzero(ph_gpu != part["ph"]))
     return slack, flips, ph_gpu.size
@@ -223,6 +240,7 @@ def sample_q_tiles(g: fo.Geometry, rng, n_interior=3):
 def score_error_ratio(run: GpuRun, head_slot, u, v):
     """max over the tile pair of |S_gpu - S_exact| / sum_c |q_c k_c| for the raw E4M3 scores."""
     g = run.g
+    assert g.NS == 1
     qt, kt, _ = run.oracle_inputs(head_slot)
     qc, _ = fo.quantize_tiles(qt[u * g.TS:(u + 1) * g.TS], fo.Geometry(1, 1, g.TS, 1, 1, g.TS))
     kc, _ = fo.quantize_tiles(kt[v * g.TS:(v + 1) * g.TS], fo.Geometry(1, 1, g.TS, 1, 1, g.TS))
@@ -233,6 +251,9 @@ def score_error_ratio(run: GpuRun, head_slot, u, v):
     got = fps.debug_scores_q8(run.shape, q8, k8, head_slot, u, v)
     run.torch.cuda.synchronize()
     got = got.double().cpu().numpy()
-    assert np.all(got[g.TS:] == 0) and np.all(got[:, g.TS:] == 0)   # padding slots: zero codes
-    got = got[:g.TS, :g.TS]
+    in_tile = run.slots[:g.TS]
+    pad = np.ones(run.tsp, dtype=bool)
+    pad[in_tile] = False
+    assert np.all(got[pad] == 0) and np.all(got[:, pad] == 0)       # padding slots: zero codes
+    got = got[in_tile][:, in_tile]
     return float(np.max(np.abs(got - exact) / np.maximum(absdot, 1e-30))), got, exact

@@ -98,6 +98,16 @@ def test_shape_validation():
         sh = fps.make_shape(2, (4, 16, 16), tile)
         assert (fps.num_tiles(sh), fps.tile_slots(sh)) == (m, slots), tile
         assert fps.packed_bytes(sh, fps.PREC_FP8) == 2 * m * slots * 128
+    # quantisation sub-tiles: each padded to whole blocks, one scale each
+    for tile, qtile, groups, slots in [((2, 8, 16), (1, 8, 16), 2, 256), ((6, 8, 8), (2, 8, 8), 3, 384),
+                                       ((4, 8, 8), (2, 4, 8), 4, 256), ((2, 4, 4), (1, 2, 4), 4, 128),
+                                       ((2, 7, 15), (1, 7, 5), 6, 384), ((2, 8, 16), (2, 8, 16), 1, 256)]:
+        sh = fps.make_shape(2, (4, 16, 16), tile, qtile=qtile)
+        assert fps.num_groups(sh) == fps.num_tiles(sh) * groups and fps.tile_slots(sh) == slots, (tile, qtile)
+    assert fps.num_groups(fps.make_shape(2, (4, 16, 16), (2, 8, 16))) == 4
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 8, 16), qtile=(1, 3, 16))) == 0   # 3 does not divide 8
+    assert "sub-tile" in fps.last_error()
+    assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 8, 16), qtile=(1, 0, 16))) == 0
     assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (33, 32, 32))) == 0   # 33792 tokens: too large
     assert "unsupported" in fps.last_error()
     assert fps.tile_slots(fps.make_shape(2, (4, 16, 16), (33, 32, 32))) == 0

@@ -89,6 +89,59 @@ def test_quantize_tiles_of_several_blocks_bit_exact(grid, tile):
     _check_quantize(run, range(2), f"multi-block {tile}")
 
 
+SUB_TILE_CASES = [
+    ((3, 13, 20), (2, 8, 16), (1, 8, 16)),      # sub-tile = one 128-slot block, 2 per tile
+    ((7, 9, 10), (6, 8, 8), (2, 8, 8)),         # 3 sub-tiles of 128 tokens
+    ((5, 9, 18), (4, 8, 8), (2, 4, 8)),         # 4 sub-tiles of 64 tokens: two 32-slot blocks each
+    ((3, 5, 6), (2, 4, 4), (1, 2, 4)),          # 4 sub-tiles of 8 tokens in a 32-slot block each
+    ((5, 16, 20), (4, 16, 16), (2, 8, 16)),     # 8 sub-tiles of 256 tokens (two 128-slot blocks each)
+    ((3, 9, 20), (2, 7, 15), (1, 7, 5)),        # 6 sub-tiles of 35 tokens in two 32-slot blocks each
+]
+
+
+@pytest.mark.parametrize("grid,tile,qtile", SUB_TILE_CASES)
+def test_quantisation_sub_tiles_layout_and_codes_bit_exact(grid, tile, qtile):
+    """Scales per sub-tile of the sparsity tile: tile order round trip, scales and codes."""
+    import torch
+    say("sub-tile quantise", grid, tile, qtile)
+    w = dataclasses.replace(synth.TINY, grid=grid, tile=tile, heads=2, n_outlier=3, config_id=19)
+    run = gu.GpuRun(w, qtile=qtile)
+    for a, t in zip(run.qkv, run.tiled):
+        got = t[0].float().cpu().numpy()
+        assert np.array_equal(got[:, run.slots], fo.tile_order(a, run.g))
+        assert np.all(got[:, run.pad_slots()] == 0)
+        assert np.array_equal(fps.tile_unorder(run.shape, t)[0].float().cpu().numpy(), a)
+    assert run.quantize()[0][1].shape[-1] == run.g.n_groups
+    _check_quantize(run, range(2), f"sub-tile {tile} {qtile}")
+    for role in range(3):                                   # fused raster entry == tiled entry
+        xq, sc = fps.quantize_tiles(run.shape, run.raster[role], role, raster=True)
+        assert torch.equal(xq, run.q8[role][0]) and torch.equal(sc, run.q8[role][1])
+
+
+@pytest.mark.parametrize("prec", [fps.PREC_FP8, fps.PREC_BF16])
+@pytest.mark.parametrize("grid,tile,qtile", SUB_TILE_CASES)
+def test_attention_with_quantisation_sub_tiles(prec, grid, tile, qtile):
+    import torch
+    say("sub-tile attention", prec, grid, tile, qtile)
+    window = (3, 3, 3)
+    w = dataclasses.replace(synth.TINY, grid=grid, tile=tile, window=window, heads=2, n_outlier=3,
+                            config_id=20)
+    run = gu.GpuRun(w, qtile=qtile)
+    out, vis = run.attn(prec, visited=True)
+    assert np.array_equal(vis.cpu().numpy().astype(bool), fo.tile_mask(run.g, window))
+    for h in range(2):
+        st = gu.compare_head(run, out, h, prec, window)
+        say("  head", h, st)
+        gu.assert_parity(st, f"{grid} {tile} {qtile} head {h}")
+    raster = run.attn(prec, raster_out=True)
+    assert torch.equal(raster, fps.tile_unorder(run.shape, out))
+    if prec == fps.PREC_FP8:                                # per-channel V with sub-tile Q/K scales
+        out = run.attn(prec, vscale=fps.VSCALE_CHANNEL)
+        st = gu.compare_head(run, out, 0, prec, window, vscale=fps.VSCALE_CHANNEL)
+        say("  per-channel V", st)
+        gu.assert_parity(st, f"{grid} {tile} {qtile} per-channel V")
+
+
 def test_quantize_special_values():
     """Ties of the exact quotient, e4m3-representable inputs, all-zero tiles, amax = 448."""
     import torch
@@ -449,6 +502,18 @@ def test_step_config_with_granularity_per_regime():
     with pytest.raises(fps.FpsError) as e:                   # inputs of the late regime at an early step
         runs[2].attn(fps.PREC_FP8, step=fps.make_step_cfg(3, 50, 0.2, 0.5, regimes))
     assert e.value.status == fps.FPS_ERR_INVALID_ARG
+    # a regime may also fix the quantisation sub-tile: same sparsity tile, finer scales
+    fine = [(fps.PREC_FP8, (1, 3, 3), (2, 8, 16), (1, 8, 16))] * 3
+    cfg = fps.make_step_cfg(44, 50, 0.2, 0.5, fine)
+    assert fps.schedule_select(cfg, with_tile=True) == fine[0]
+    with pytest.raises(fps.FpsError):
+        runs[2].attn(fps.PREC_FP8, step=cfg)                 # quantised per tile, regime wants per sub-tile
+    w = dataclasses.replace(synth.TINY, grid=(7, 13, 20), tile=(2, 8, 16), window=(1, 3, 3), heads=1,
+                            n_outlier=3, config_id=17)
+    run = gu.GpuRun(w, qtile=(1, 8, 16))
+    st = gu.compare_head(run, run.attn(fps.PREC_FP8, step=cfg), 0, fps.PREC_FP8, (1, 3, 3))
+    say("  sub-tile regime", st)
+    gu.assert_parity(st, "sub-tile regime")
 
 
 # ---- full-size shapes, sampled against the oracle ---------------------------------------------
