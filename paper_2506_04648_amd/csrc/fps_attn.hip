@@ -121,7 +121,7 @@ __device__ __forceinline__ int tile_class(const G_& g, int t, int h, int w) {
 // transposes its 16-row blocks through a private 16 KB LDS region and writes whole rows
 // (256 or 512 contiguous bytes).  The caller guarantees that no wave still reads the LDS buffers.
 template <int TS>
-__device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int jq, int ucls, int wave,
+__device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int jq, int KBS, int ucls, int wave,
                                            int lane, const v4f (&acc)[2][8], const float (&inv)[2],
                                            uint8_t* wave_lds, const float* ch_scale = nullptr) {
     const auto& G = a.g;
@@ -129,6 +129,10 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
     const int row_bytes = a.out_f32 ? 512 : 256;
     const int pitch = row_bytes + 16;                      // padding keeps the column writes off one bank
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
+    // the block lies in ONE sub-tile: decode that once, the rows then cost two divisions each
+    const int sub = jq / KBS;
+    const SubTile so = sub_tile_origin(G, sub);
+    const int slot0 = (jq - sub * KBS) * TS;               // the block's first slot within the sub-tile
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
@@ -152,18 +156,17 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
         const int rows_per_pass = 64 / lanes_per_row;
         for (int r0 = 0; r0 < 16; r0 += rows_per_pass) {
             const int r = r0 + lane / lanes_per_row, chunk = lane % lanes_per_row;
-            const int rr = jq * TS + wave * 32 + qb * 16 + r;   // the row's slot in its tile (TS: block size)
-            const bool valid = slot_is_token(G, ucls, rr);
+            const int in_block = wave * 32 + qb * 16 + r;       // TS: block size
+            int rt = 0, rh = 0, rw = 0;
+            const bool valid = sub_slot_coords(G, so, slot0 + in_block, &rt, &rh, &rw) &&
+                               coords_in_class(G, ucls, rt, rh, rw);
             uint4 val = *reinterpret_cast<const uint4*>(wave_lds + r * pitch + chunk * 16);
             size_t row;
             if (a.out_raster) {
                 if (!valid) continue;
-                int rt = 0, rh = 0, rw = 0;
-                const int sub = rr / G.QSP;
-                sub_slot_coords(G, sub, rr - sub * G.QSP, &rt, &rh, &rw);
                 row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
             } else {
-                row = ((size_t)bh * G.M + u) * G.TSP + rr;
+                row = ((size_t)bh * G.M + u) * G.TSP + (size_t)jq * TS + in_block;
                 if (!valid) val = make_uint4(0, 0, 0, 0);
             }
             reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) + row * row_bytes)[chunk] = val;
@@ -227,9 +230,10 @@ __device__ __forceinline__ void zero_block_rows(const AttnArgs& a, int bh, int u
 template <int TS>
 __device__ __forceinline__ void block_ballots(const Geom& G, int cls, int js, int jb, int lane,
                                               uint64_t (&bm)[(TS + 63) / 64]) {
+    const SubTile so = sub_tile_origin(G, js);
 #pragma unroll
     for (int h = 0; h < (TS + 63) / 64; ++h)
-        bm[h] = __ballot(sub_slot_is_token(G, cls, js, jb * TS + 64 * h + lane));
+        bm[h] = __ballot(sub_slot_is_token(G, cls, so, jb * TS + 64 * h + lane));
 }
 
 __device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
@@ -559,7 +563,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
     __syncthreads();                                       // all waves are done with the staged tiles
-    store_rows<TS>(a, bh, u, jq, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+    store_rows<TS>(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
                    &lds[0][0] + wave * kStoreRegionBytes, VCH ? a.sv + (size_t)bh * 128 : nullptr);
 }
 
@@ -830,7 +834,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;
     }
     __syncthreads();                                       // all waves are done with the staged tiles
-    store_rows<TS>(a, bh, u, jq, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+    store_rows<TS>(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
                    &lds[0][0] + wave * kStoreRegionBytes);
 }
 

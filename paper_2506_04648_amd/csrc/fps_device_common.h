@@ -44,16 +44,23 @@ __device__ __forceinline__ const uint4* token_row(const uint4* x, const Geom& g,
     return x + ((((o.bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);
 }
 
-// max of the 15-bit magnitude patterns of 8 bf16 values (|x| of bf16 orders like that integer)
-__device__ __forceinline__ uint32_t amax_bits16(const uint4& v, uint32_t m) {
+// max of the 15-bit magnitude patterns of 8 bf16 values (|x| of bf16 orders like that integer),
+// two patterns per instruction: the running maximum m2 holds one candidate in each 16-bit half
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t amax_pairs16(const uint4& v, uint32_t m2) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    u16x2 m = __builtin_bit_cast(u16x2, m2);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
-        m = lo > m ? lo : m;
-        m = hi > m ? hi : m;
-    }
-    return m;
+    for (int i = 0; i < 4; ++i) m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2, w[i] & 0x7FFF7FFFu));
+    return __builtin_bit_cast(uint32_t, m);
+}
+__device__ __forceinline__ uint32_t amax_of_pairs(uint32_t m2) {        // the larger half
+    const uint32_t lo = m2 & 0xFFFFu, hi = m2 >> 16;
+    return lo > hi ? lo : hi;
+}
+__device__ __forceinline__ uint32_t amax_bits16(const uint4& v, uint32_t m) {
+    const uint32_t p = amax_of_pairs(amax_pairs16(v, 0u));
+    return p > m ? p : m;
 }
 
 // workgroup-wide max of m over 256 threads (red: 4 words of LDS); every thread gets the result

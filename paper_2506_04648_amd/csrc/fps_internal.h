@@ -35,32 +35,43 @@ struct Geom {
     int kb_last;
 };
 
-// In-tile coordinates (rt, rh, rw) of slot rr of sub-tile s; false if the slot is padding of the
-// sub-tile (rr >= QS).
-__host__ __device__ inline bool sub_slot_coords(const Geom& g, int s, int rr, int* rt, int* rh, int* rw) {
-    if (rr >= g.QS) return false;
+// In-tile coordinates of the first token of sub-tile s (decoded once per block: s is the same
+// for all slots of a block).
+struct SubTile { int t0, h0, w0; };
+__host__ __device__ inline SubTile sub_tile_origin(const Geom& g, int s) {
     const int layer = g.nsH * g.nsW;
     const int st = s / layer, srem = s - st * layer;
     const int sh = srem / g.nsW, sw = srem - sh * g.nsW;
+    return SubTile{st * g.Qt, sh * g.Qh, sw * g.Qw};
+}
+
+// In-tile coordinates (rt, rh, rw) of slot rr of the sub-tile with origin o; false if the slot is
+// padding of the sub-tile (rr >= QS).
+__host__ __device__ inline bool sub_slot_coords(const Geom& g, const SubTile& o, int rr, int* rt, int* rh, int* rw) {
+    if (rr >= g.QS) return false;
     const int plane = g.Qh * g.Qw;
     const int a = rr / plane, rem = rr - a * plane;
     const int b = rem / g.Qw, c = rem - b * g.Qw;
-    *rt = st * g.Qt + a; *rh = sh * g.Qh + b; *rw = sw * g.Qw + c;
+    *rt = o.t0 + a; *rh = o.h0 + b; *rw = o.w0 + c;
     return true;
 }
 
-// slot rr of sub-tile s of a tile of boundary class c holds a real token
-__host__ __device__ inline bool sub_slot_is_token(const Geom& g, int c, int s, int rr) {
-    int rt, rh, rw;
-    if (!sub_slot_coords(g, s, rr, &rt, &rh, &rw)) return false;
+// in-tile coordinates (rt, rh, rw) lie inside the real extent of a tile of boundary class c
+__host__ __device__ inline bool coords_in_class(const Geom& g, int c, int rt, int rh, int rw) {
     return rt < ((c & 4) ? g.lastT : g.Tt) && rh < ((c & 2) ? g.lastH : g.Th) &&
            rw < ((c & 1) ? g.lastW : g.Tw);
+}
+
+// slot rr of the sub-tile with origin o, in a tile of boundary class c, holds a real token
+__host__ __device__ inline bool sub_slot_is_token(const Geom& g, int c, const SubTile& o, int rr) {
+    int rt, rh, rw;
+    return sub_slot_coords(g, o, rr, &rt, &rh, &rw) && coords_in_class(g, c, rt, rh, rw);
 }
 
 // slot r (0 .. TSP-1) of a tile of boundary class c holds a real token
 __host__ __device__ inline bool slot_is_token(const Geom& g, int c, int r) {
     const int s = r / g.QSP;
-    return sub_slot_is_token(g, c, s, r - s * g.QSP);
+    return sub_slot_is_token(g, c, sub_tile_origin(g, s), r - s * g.QSP);
 }
 
 void set_error(const char* fmt, ...);

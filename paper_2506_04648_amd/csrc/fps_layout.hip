@@ -35,7 +35,7 @@ __global__ void tile_order_kernel(const uint4* __restrict__ in, uint4* __restric
     const int uw = u % g.nW, uh = (u / g.nW) % g.nH, ut = u / (g.nW * g.nH);
     const int s = r / g.QSP;
     int rt = 0, rh = 0, rw = 0;
-    const bool slot_used = sub_slot_coords(g, s, r - s * g.QSP, &rt, &rh, &rw);
+    const bool slot_used = sub_slot_coords(g, sub_tile_origin(g, s), r - s * g.QSP, &rt, &rh, &rw);
     const int t = ut * g.Tt + rt, h = uh * g.Th + rh, w = uw * g.Tw + rw;
     uint4 val = make_uint4(0, 0, 0, 0);
     if (slot_used && t < g.T && h < g.H && w < g.W) {

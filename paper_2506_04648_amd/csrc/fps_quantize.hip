@@ -33,22 +33,27 @@ __device__ __forceinline__ float quotient_for_rne(float x, float s) {
     return __builtin_fminf(__builtin_fmaxf(q, -448.0f), 448.0f);
 }
 
-// Same result as quotient_for_rne(x, s), cheaper on the common path: x * (1/s) is within two float
-// ulps of the exact quotient, so the rounding can only differ when an E4M3 midpoint lies within a
-// few ulps of the product; only then (and in the subnormal range of the format, where the grid is
-// absolute) the exact routine runs.  rs = 1/s, correctly rounded.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Same result as quotient_for_rne(x, s), cheaper on the common path: x * (1/s) is within three
+// float ulps of the exact quotient, so the rounding can only differ when an E4M3 midpoint lies
+// within a few ulps of the product; only then (and in the subnormal range of the format, where
+// the grid is absolute) the exact routine runs.  rs = 1/s, correctly rounded.
+// The product is formed as fma(x, 1/s, tiny): a zero input (padding, common) then gives `tiny`,
+// which encodes as 0 like the exact path would, without taking that path; for non-zero inputs the
+// addend is far below an ulp.  No clamp is needed on the common path: |x| <= amax makes the
+// product at most 448 (1 + 2^-22), far below the next rounding boundary (464).
 __device__ __forceinline__ float quotient_fast(float x, float s, float rs) {
-    const float q = x * rs;
+    const float q = __builtin_fmaf(x, rs, 1.3e-30f);
     const uint32_t qb = __float_as_uint(q);
     const uint32_t low = (qb & 0xFFFFFu) - (0x80000u - 4u);          // distance to a midpoint pattern
     const bool near_mid = low <= 8u;
-    const bool subnormal = (qb & 0x7FFFFFFFu) < 0x3C800000u;          // |q| < 2^-6
+    // 2^-90 <= |q| < 2^-6 (below 2^-90, which includes `tiny`, the code is 0 either way)
+    const bool subnormal = ((qb << 1) - 0x25000000u) < (0x79000000u - 0x25000000u);
     if (__builtin_expect(near_mid || subnormal, 0)) return quotient_for_rne(x, s);
-    return __builtin_fminf(__builtin_fmaxf(q, -448.0f), 448.0f);
+    return q;
 }
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
 // 16 bf16 (two uint4) -> 16 E4M3 codes (one uint4)
 __device__ __forceinline__ uint4 encode16(const uint4& lo, const uint4& hi, float s) {
@@ -121,9 +126,10 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __rest
         lo[i] = make_uint4(0, 0, 0, 0);
         hi[i] = lo[i];
         if (row) { lo[i] = row[2 * (unit & 7)]; hi[i] = row[2 * (unit & 7) + 1]; }
-        mb = amax_bits16(lo[i], mb);
-        mb = amax_bits16(hi[i], mb);
+        mb = amax_pairs16(lo[i], mb);
+        mb = amax_pairs16(hi[i], mb);
     }
+    mb = amax_of_pairs(mb);
     float amax;
     if (tile_amax) {
         amax = tile_amax[blk / g.KBS];
