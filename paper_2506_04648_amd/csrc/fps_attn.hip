@@ -1,8 +1,10 @@
 // Sliding-tile attention forward (Eq. 2-3, Sec. 3.2 aggregation; Algorithm 1 steps 4-5).
 //
-// One workgroup per (bh, query tile); wave w owns query rows 32w..32w+31 of the tile as two
-// 16-row blocks.  The kernel walks the box of key tiles given by Eq. 2 -- tile pairs outside the
-// box are never scheduled -- staging each K and V tile through LDS.  Scores are produced
+// One workgroup per (bh, query tile, block of BS = 128 or 32 query slots of the tile); wave w owns
+// query rows 32w..32w+31 of the block as two 16-row blocks.  The kernel walks the box of key tiles
+// given by Eq. 2 -- tile pairs outside the box are never scheduled -- block by block, staging each
+// K and V block through LDS.  A tile of at most BS tokens is one block; larger tiles, and tiles cut
+// into quantisation sub-tiles, are several blocks (kernels instantiated with MB = true).  Scores are produced
 // transposed, S^T = K Q^T, so that a lane's accumulator holds one query row and the keys
 // 16b + 4g + 0..3; after the softmax those registers are, unchanged, the second operand of the
 // PV product O^T = V^T P^T (see the packed layouts in fps_layout.hip).
@@ -120,7 +122,7 @@ __device__ __forceinline__ int tile_class(const G_& g, int t, int h, int w) {
 // accumulator, so direct stores would be 8- or 16-byte pieces of many rows; instead each wave
 // transposes its 16-row blocks through a private 16 KB LDS region and writes whole rows
 // (256 or 512 contiguous bytes).  The caller guarantees that no wave still reads the LDS buffers.
-template <int TS>
+template <int BS>
 __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int jq, int KBS, int ucls, int wave,
                                            int lane, const v4f (&acc)[2][8], const float (&inv)[2],
                                            uint8_t* wave_lds, const float* ch_scale = nullptr) {
@@ -132,7 +134,7 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
     // the block lies in ONE sub-tile: decode that once, the rows then cost two divisions each
     const int sub = jq / KBS;
     const SubTile so = sub_tile_origin(G, sub);
-    const int slot0 = (jq - sub * KBS) * TS;               // the block's first slot within the sub-tile
+    const int slot0 = (jq - sub * KBS) * BS;               // the block's first slot within the sub-tile
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
@@ -156,7 +158,7 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
         const int rows_per_pass = 64 / lanes_per_row;
         for (int r0 = 0; r0 < 16; r0 += rows_per_pass) {
             const int r = r0 + lane / lanes_per_row, chunk = lane % lanes_per_row;
-            const int in_block = wave * 32 + qb * 16 + r;       // TS: block size
+            const int in_block = wave * 32 + qb * 16 + r;       // BS: block size
             int rt = 0, rh = 0, rw = 0;
             const bool valid = sub_slot_coords(G, so, slot0 + in_block, &rt, &rh, &rw) &&
                                coords_in_class(G, ucls, rt, rh, rw);
@@ -166,7 +168,7 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
                 if (!valid) continue;
                 row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
             } else {
-                row = ((size_t)bh * G.M + u) * G.TSP + (size_t)jq * TS + in_block;
+                row = ((size_t)bh * G.M + u) * G.TSP + (size_t)jq * BS + in_block;
                 if (!valid) val = make_uint4(0, 0, 0, 0);
             }
             reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) + row * row_bytes)[chunk] = val;
@@ -214,26 +216,26 @@ struct TileWalk {
 };
 
 // A query block that holds padding only: its rows of a tile-ordered output are zero, a raster
-// output has no such rows.  TS: block size, NTHR: threads of the workgroup.
-template <int TS, int NTHR>
+// output has no such rows.  BS: block size, NTHR: threads of the workgroup.
+template <int BS, int NTHR>
 __device__ __forceinline__ void zero_block_rows(const AttnArgs& a, int bh, int u, int jq) {
     if (a.out_raster) return;
     const int row_bytes = a.out_f32 ? 512 : 256;
     uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) +
-                                          (((size_t)bh * a.g.M + u) * a.g.TSP + (size_t)jq * TS) * row_bytes);
-    for (int i = threadIdx.x; i < TS * (row_bytes / 16); i += NTHR) dst[i] = make_uint4(0, 0, 0, 0);
+                                          (((size_t)bh * a.g.M + u) * a.g.TSP + (size_t)jq * BS) * row_bytes);
+    for (int i = threadIdx.x; i < BS * (row_bytes / 16); i += NTHR) dst[i] = make_uint4(0, 0, 0, 0);
 }
 
-// Validity of the TS slots of block jb of sub-tile js of a tile of class cls as wave-wide ballots:
+// Validity of the BS slots of block jb of sub-tile js of a tile of class cls as wave-wide ballots:
 // bit i of word h says whether slot 64h + i of the block is a real token.  Evaluated
 // arithmetically, so that tiles of any size need no table.
-template <int TS>
+template <int BS>
 __device__ __forceinline__ void block_ballots(const Geom& G, int cls, int js, int jb, int lane,
-                                              uint64_t (&bm)[(TS + 63) / 64]) {
+                                              uint64_t (&bm)[(BS + 63) / 64]) {
     const SubTile so = sub_tile_origin(G, js);
 #pragma unroll
-    for (int h = 0; h < (TS + 63) / 64; ++h)
-        bm[h] = __ballot(sub_slot_is_token(G, cls, so, jb * TS + 64 * h + lane));
+    for (int h = 0; h < (BS + 63) / 64; ++h)
+        bm[h] = __ballot(sub_slot_is_token(G, cls, so, jb * BS + 64 * h + lane));
 }
 
 __device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
@@ -270,13 +272,13 @@ __device__ __forceinline__ void dma_chunk(const void* gsrc, uint32_t lane_off, u
 // K(i+2) and V(i) stream into LDS during iteration i; one barrier per iteration.
 // VCH: V carries one scale per channel (the paper's variant) instead of one per tile; the PV MFMA
 // then accumulates straight into O and the scales are applied once in the epilogue.
-template <int TS, bool VCH, bool MB>
-__global__ __launch_bounds__(TS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int BS, bool VCH, bool MB>
+__global__ __launch_bounds__(BS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_fp8_kernel(AttnArgs a, MaskTables) {
-    constexpr int NB = TS / 16;
-    constexpr int NTHR = TS * 2;
-    constexpr int CPT = (TS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
-    constexpr int TILE_BYTES = TS * 128;
+    constexpr int NB = BS / 16;
+    constexpr int NTHR = BS * 2;
+    constexpr int CPT = (BS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
+    constexpr int TILE_BYTES = BS * 128;
     __shared__ __attribute__((aligned(16))) uint8_t lds[4][TILE_BYTES];   // K even, K odd, V even, V odd
     const Geom& G = a.g;
     const int KB = MB ? G.KB : 1;                          // blocks per tile; 1 is a compile-time fact
@@ -288,7 +290,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
     if (MB && jq >= (ut == G.nT - 1 ? KB_LAST : KB)) {      // a query block of padding only
-        zero_block_rows<TS, TS * 2>(a, bh, u, jq);
+        zero_block_rows<BS, BS * 2>(a, bh, u, jq);
         return;
     }
     const size_t tile0 = (size_t)bh * G.M;
@@ -303,7 +305,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wave * 32 + qb * 16 + n;
         const uint4* p = reinterpret_cast<const uint4*>(
-            a.q + (((tile0 + u) * KB + jq) * TS + row) * 128 + 32 * g);
+            a.q + (((tile0 + u) * KB + jq) * BS + row) * 128 + 32 * g);
         qop[qb] = make_v8i(p[0], p[1]);
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) acc[qb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -345,7 +347,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
                 kop, qop[qb], v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
     };
     auto load_v = [&](const uint8_t* ldsV, int cb) FPS_INLINE {
-        if constexpr (TS == 128) {
+        if constexpr (BS == 128) {
             const uint4* v4 = reinterpret_cast<const uint4*>(ldsV);
             return make_v8i(v4[(cb * 2 + 0) * 64 + lane], v4[(cb * 2 + 1) * 64 + lane]);
         } else {
@@ -359,7 +361,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         for (int qb = 0; qb < 2; ++qb) {
             const v4f c_in = VCH ? acc[qb][cb] : v4f{0.f, 0.f, 0.f, 0.f};
             v4f r;
-            if constexpr (TS == 128) {
+            if constexpr (BS == 128) {
                 r = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(vop, pb[qb], c_in, 0, 0, 0, 0, 0, 0);
             } else {
                 const long va = (long)(uint32_t)vop[0] | ((long)(uint32_t)vop[1] << 32);
@@ -392,11 +394,11 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
                     s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
                 }
         } else {                                           // block jk of a larger tile
-            uint64_t bm[(TS + 63) / 64];
-            block_ballots<TS>(G, cls, js, jb, lane, bm);
+            uint64_t bm[(BS + 63) / 64];
+            block_ballots<BS>(G, cls, js, jb, lane, bm);
             bool all = true;
 #pragma unroll
-            for (int h = 0; h < (TS + 63) / 64; ++h) all = all && (bm[h] | (TS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
+            for (int h = 0; h < (BS + 63) / 64; ++h) all = all && (bm[h] | (BS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
             if (all) return;                               // most blocks of a boundary tile are whole
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -563,7 +565,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
     __syncthreads();                                       // all waves are done with the staged tiles
-    store_rows<TS>(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+    store_rows<BS>(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
                    &lds[0][0] + wave * kStoreRegionBytes, VCH ? a.sv + (size_t)bh * 128 : nullptr);
 }
 
@@ -577,14 +579,14 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 // ---------------------------------------------------------------------------------------------
 union Bf16x8 { uint4 u; v8bf v; v8h h; };
 
-template <int TS, bool MB>
-__global__ __launch_bounds__(TS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int BS, bool MB>
+__global__ __launch_bounds__(BS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_bf16_kernel(AttnArgs a, MaskTables) {
-    constexpr int NB = TS / 16;
-    constexpr int NKK = TS / 32;
-    constexpr int NTHR = TS * 2;
-    constexpr int TILE_BYTES = TS * 256;
-    constexpr int CPT = (TS * 16) / NTHR;                  // 16-byte chunks per thread per operand tile (8)
+    constexpr int NB = BS / 16;
+    constexpr int NKK = BS / 32;
+    constexpr int NTHR = BS * 2;
+    constexpr int TILE_BYTES = BS * 256;
+    constexpr int CPT = (BS * 16) / NTHR;                  // 16-byte chunks per thread per operand tile (8)
     __shared__ __attribute__((aligned(16))) uint8_t lds[2][TILE_BYTES];   // K, V
     const Geom& G = a.g;
     const int KB = MB ? G.KB : 1;                          // blocks per tile; 1 is a compile-time fact
@@ -596,7 +598,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
     if (MB && jq >= (ut == G.nT - 1 ? KB_LAST : KB)) {      // a query block of padding only
-        zero_block_rows<TS, TS * 2>(a, bh, u, jq);
+        zero_block_rows<BS, BS * 2>(a, bh, u, jq);
         return;
     }
     const size_t tile0 = (size_t)bh * G.M;
@@ -610,7 +612,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wave * 32 + qb * 16 + n;
-        const uint4* p = reinterpret_cast<const uint4*>(a.q + (((tile0 + u) * KB + jq) * TS + row) * 256);
+        const uint4* p = reinterpret_cast<const uint4*>(a.q + (((tile0 + u) * KB + jq) * BS + row) * 256);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qop[qb][ks].u = p[ks * 4 + g];
 #pragma unroll
@@ -683,11 +685,11 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
                     s[1][b][r] = select_lanes(lm, s[1][b][r], -INFINITY);
                 }
         } else {                                           // block jk of a larger tile
-            uint64_t bm[(TS + 63) / 64];
-            block_ballots<TS>(G, cls, js, jb, lane, bm);
+            uint64_t bm[(BS + 63) / 64];
+            block_ballots<BS>(G, cls, js, jb, lane, bm);
             bool all = true;
 #pragma unroll
-            for (int h = 0; h < (TS + 63) / 64; ++h) all = all && (bm[h] | (TS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
+            for (int h = 0; h < (BS + 63) / 64; ++h) all = all && (bm[h] | (BS >= 64 ? 0ull : ~0xFFFFFFFFull)) == ~0ull;
             if (all) return;                               // most blocks of a boundary tile are whole
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -834,21 +836,21 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;
     }
     __syncthreads();                                       // all waves are done with the staged tiles
-    store_rows<TS>(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+    store_rows<BS>(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
                    &lds[0][0] + wave * kStoreRegionBytes);
 }
 
 // Debug: raw E4M3 score accumulators sum_c q_ic * k_jc of one tile pair, produced by the same MFMA
-// instruction and operand layouts as attn_fp8_kernel; out[i*TS + j], query-major.
-template <int TS>
-__global__ __launch_bounds__(TS * 2) void scores_fp8_kernel(const uint8_t* __restrict__ q_tile,
+// instruction and operand layouts as attn_fp8_kernel; out[i*BS + j], query-major.
+template <int BS>
+__global__ __launch_bounds__(BS * 2) void scores_fp8_kernel(const uint8_t* __restrict__ q_tile,
                                                             const uint8_t* __restrict__ k_tile,
                                                             float* __restrict__ out_tile, int out_pitch) {
-    constexpr int NB = TS / 16;
+    constexpr int NB = BS / 16;
     // workgroup (x, y) = (key block, query block) of the tile pair
-    const uint8_t* q = q_tile + (size_t)blockIdx.y * TS * 128;
-    const uint8_t* k = k_tile + (size_t)blockIdx.x * TS * 128;
-    float* out = out_tile + (size_t)blockIdx.y * TS * out_pitch + (size_t)blockIdx.x * TS;
+    const uint8_t* q = q_tile + (size_t)blockIdx.y * BS * 128;
+    const uint8_t* k = k_tile + (size_t)blockIdx.x * BS * 128;
+    float* out = out_tile + (size_t)blockIdx.y * BS * out_pitch + (size_t)blockIdx.x * BS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, n = lane & 15;
     const uint4* k4 = reinterpret_cast<const uint4*>(k);
 #pragma unroll

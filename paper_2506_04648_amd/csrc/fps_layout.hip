@@ -1,17 +1,18 @@
 // Layout kernels of libfps: raster <-> tile order (Sec. 3.2 step (1)), the BF16 operand packing,
 // and the debug unpacking of packed E4M3 tensors.  All of them are pure data movement.
 //
-// Packed operand layouts, per (bh, tile) block.  "lane" = 16*g + n is the MFMA lane that consumes
-// the chunk: n selects the row of the 16-row operand block, g the group of contraction slots.
-//   E4M3 Q : row-major [token][128]                                    (TS*128 bytes)
+// Packed operand layouts, per block of BS = 128 or 32 slots (a tile is one or several blocks).
+// "lane" = 16*g + n is the MFMA lane that consumes the chunk: n selects the row of the 16-row
+// operand block, g the group of contraction slots.
+//   E4M3 Q : row-major [token][128]                                    (BS*128 bytes)
 //   E4M3 K : 16-byte chunk ((b*2 + h)*64 + lane) = K[16b + n][32g + 16h + 0..15]
-//   E4M3 V : TS=128: 16-byte chunk ((cb*2 + h)*64 + lane), byte j -> slot s = 16h + j
-//            TS=32 :  8-byte chunk (cb*64 + lane),          byte j -> slot s = j
+//   E4M3 V : BS=128: 16-byte chunk ((cb*2 + h)*64 + lane), byte j -> slot s = 16h + j
+//            BS=32 :  8-byte chunk (cb*64 + lane),          byte j -> slot s = j
 //            holding V[key(g,s)][16cb + n] with key(g,s) = 16*(s/4) + 4g + s%4
-//   BF16 Q : row-major [token][128]                                    (TS*256 bytes)
+//   BF16 Q : row-major [token][128]                                    (BS*256 bytes)
 //   BF16 K : 16-byte chunk ((b*4 + ks)*64 + lane) = K[16b + n][32ks + 8g + 0..7]
 //   BF16 V : 16-byte chunk ((kk*8 + cb)*64 + lane), element e -> V[32kk + key(g,e)][16cb + n],
-//            stored as fp16 after an exact per-tile power-of-two scaling (see pack_bf16_kernel)
+//            stored as fp16 after an exact power-of-two scaling per scale group (see pack_bf16_kernel)
 // key(g,s) is the key that slot s of lane group g holds after a 16x16 MFMA wrote S^T = K Q^T: the
 // accumulator of lane (n,g) for key block b has keys 16b + 4g + 0..3, so P^T can be fed back as
 // the second operand of the PV product without any cross-lane movement.
@@ -126,13 +127,13 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
 }
 
 // ---- debug unpack of E4M3 tensors ---------------------------------------------------------------
-template <int TS>                                         // TS here: tokens per BLOCK
+template <int BS>
 __global__ __launch_bounds__(256) void unpack_q8_kernel(const uint8_t* __restrict__ in,
                                                         uint8_t* __restrict__ out, int role) {
     const long long blk = blockIdx.x;
-    const uint8_t* src = in + blk * (TS * 128);
-    uint8_t* dst = out + blk * (TS * 128);
-    for (int i = threadIdx.x; i < TS * 128; i += 256) {
+    const uint8_t* src = in + blk * (BS * 128);
+    uint8_t* dst = out + blk * (BS * 128);
+    for (int i = threadIdx.x; i < BS * 128; i += 256) {
         const int j = i >> 7, c = i & 127;                 // token, channel of the row-major output
         int off;
         if (role == FPS_ROLE_Q) {
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(256) void unpack_q8_kernel(const uint8_t* __restric
         } else {
             const int cb = c >> 4, n = c & 15;
             const int gg = (j >> 2) & 3, s = 4 * (j >> 4) + (j & 3);   // inverse of key_of_slot
-            if (TS == 128) off = ((cb * 2 + (s >> 4)) * 64 + gg * 16 + n) * 16 + (s & 15);
+            if (BS == 128) off = ((cb * 2 + (s >> 4)) * 64 + gg * 16 + n) * 16 + (s & 15);
             else           off = (cb * 64 + gg * 16 + n) * 8 + s;
         }
         dst[i] = src[off];

@@ -1,6 +1,7 @@
-// Per-tile amax -> scale -> E4M3 encode (Sec. 3.2, Eq. 4-5; Algorithm 1 step 2), writing the
-// packed operand layouts described in fps_layout.hip.  One workgroup of 256 threads per
-// (bh, tile); the pass is HBM-bound (2 bytes read, 1 byte written per element).
+// Per-group amax -> scale -> E4M3 encode (Sec. 3.2, Eq. 4-5; Algorithm 1 step 2), writing the
+// packed operand layouts described in fps_layout.hip.  A scale group is a 3D tile, or a
+// quantisation sub-tile of it.  One workgroup of 256 threads per block of BS slots; the pass is
+// HBM-bound (2 bytes read, 1 byte written per element).
 #include "fps_device_common.h"
 
 namespace fps {
@@ -99,8 +100,8 @@ __device__ __forceinline__ void write_v_block(const uint8_t* stage, uint4* dst, 
     }
 }
 
-// One workgroup of 256 threads per block of BS tokens.  A tile of one block (KB = 1) is handled in
-// a single pass: amax, scale, encode.  For larger tiles the tile amax comes from block_amax_kernel
+// One workgroup of 256 threads per block of BS slots.  A scale group of one block (KBS = 1) is
+// handled in a single pass: amax, scale, encode.  For larger groups the amax comes from block_amax_kernel
 // (tile_amax != nullptr) and this kernel only encodes.
 // RASTER: x is the raster tensor [BH,T,H,W,128] and the block's tokens are gathered from it (padded
 // slots read as zero), which fuses the tile ordering of Sec. 3.2 step (1) into this pass.
@@ -257,7 +258,7 @@ int launch_quantize(const Geom& g, const void* x, int raster, int role, int vsca
     const uint4* xi = (const uint4*)x;
     uint8_t* xo = (uint8_t*)xq;
     const float* tile_amax = nullptr;
-    if (g.KBS > 1) {                     // tile amax over several blocks first; `scales` holds it meanwhile
+    if (g.KBS > 1) {                    // group amax over several blocks first; `scales` holds it meanwhile
         clear_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>((uint32_t*)scales, ntiles);
         if (raster) block_amax_kernel<true><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
         else        block_amax_kernel<false><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);

@@ -386,6 +386,49 @@ def test_two_runs_are_bit_identical(tiny):
     assert torch.equal(a, b)
 
 
+def _random_case(rng):
+    """A random small configuration: grid, tile, optional quantisation sub-tile, window, edge rule,
+    precision, V scale granularity."""
+    def divisors(n):
+        return [d for d in range(1, n + 1) if n % d == 0]
+    while True:
+        tile = tuple(int(rng.choice(c)) for c in ([1, 2, 3, 4, 6], [1, 2, 4, 5, 8, 16], [2, 4, 5, 8, 16]))
+        ts = tile[0] * tile[1] * tile[2]
+        if not 8 <= ts <= 512:
+            continue
+        n_tiles = (int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 5)))
+        grid = tuple(max(1, n * t - int(rng.integers(0, t))) for n, t in zip(n_tiles, tile))
+        if grid[0] * grid[1] * grid[2] > 2600:
+            continue
+        qtile = None
+        if rng.random() < 0.4:
+            qtile = tuple(int(rng.choice(divisors(t))) for t in tile)
+        window = tuple(int(rng.integers(1, 6)) for _ in range(3))
+        if rng.random() < 0.3:
+            window += (fps.EDGE_SHIFT,)
+        prec = fps.PREC_FP8 if rng.random() < 0.7 else fps.PREC_BF16
+        vscale = fps.VSCALE_CHANNEL if (prec == fps.PREC_FP8 and rng.random() < 0.3) else fps.VSCALE_TILE
+        return grid, tile, qtile, window, prec, vscale
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configurations(seed):
+    """Seeded random shapes, tiles, sub-tiles, windows, edge rules and modes against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    grid, tile, qtile, window, prec, vscale = _random_case(rng)
+    say("random case", seed, grid, tile, qtile, window, prec, vscale)
+    w = dataclasses.replace(synth.TINY, grid=grid, tile=tile, window=window[:3], heads=1, n_outlier=3,
+                            config_id=100 + seed)
+    run = gu.GpuRun(w, qtile=qtile)
+    out, vis = run.attn(prec, window=window, visited=True, vscale=vscale)
+    assert np.array_equal(vis.cpu().numpy().astype(bool), fo.tile_mask(run.g, window))
+    if prec == fps.PREC_FP8:
+        _check_quantize(run, [0], f"random {seed}") if vscale == fps.VSCALE_TILE else None
+    st = gu.compare_head(run, out, 0, prec, window, vscale=vscale)
+    say("  ", st)
+    gu.assert_parity(st, f"random case {seed}: {grid} {tile} {qtile} {window} {prec} {vscale}")
+
+
 def test_batch_and_heads_are_interchangeable():
     """Tensors are indexed by b*heads + h: (B=2, heads=3) equals (B=1, heads=6) bit for bit."""
     import torch
