@@ -53,8 +53,8 @@ def main():
                          "the sparse window, the shifted-window edge rule, other tile shapes")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (heads shard across GPUs without any "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (heads are independent and would shard across "
+              "GPUs without any exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -36,9 +36,8 @@ __device__ __forceinline__ const uint4* token_row(const uint4* x, const Geom& g,
     if (!RASTER) return x + ((long long)blk * g.BS + r) * 16;
     const int slot = o.slot0 + r;
     if (slot >= g.QS) return nullptr;                    // slots past the sub-tile's tokens are padding
-    const int plane = g.Qh * g.Qw;
-    const int rt = slot / plane, rem = slot - rt * plane;
-    const int rh = rem / g.Qw, rw = rem - rh * g.Qw;
+    const int rt = div_by_recip(slot, g.inv_qplane), rem = slot - rt * (g.Qh * g.Qw);
+    const int rh = div_by_recip(rem, g.inv_qw), rw = rem - rh * g.Qw;
     const int t = o.t0 + rt, h = o.h0 + rh, w = o.w0 + rw;
     if (t >= g.T || h >= g.H || w >= g.W) return nullptr;
     return x + ((((o.bh * g.T + t) * g.H + h) * (long long)g.W + w) * 16);

@@ -81,6 +81,8 @@ int check_shape(const fps_shape* s, Geom* g) {
     g->Qt = qt; g->Qh = qh; g->Qw = qw;
     g->nsT = s->Tt / qt; g->nsH = s->Th / qh; g->nsW = s->Tw / qw;
     g->NS = ns; g->QS = qs;
+    g->inv_qplane = 1.0f / (float)(qh * qw);
+    g->inv_qw = 1.0f / (float)qw;
     g->BS = bs; g->KBS = kbs; g->QSP = kbs * bs; g->KB = (int)kb; g->TSP = (int)kb * bs;
     g->lastT = s->T - (nT - 1) * s->Tt;
     g->lastH = s->H - (nH - 1) * s->Th;

@@ -157,3 +157,15 @@ def test_device_entry_points_validate_before_launching():
     cfg = fps.make_step_cfg(5, 50, 0.2, 0.5, [(1, (3, 3, 3), (shape.Tt + 1, shape.Th, shape.Tw))] * 3)
     assert L.fps_attn_fwd(S, None, 1, ctypes.byref(cfg), *args) == fps.FPS_ERR_INVALID_ARG
     assert "selects tile" in fps.last_error()
+
+
+def test_reciprocal_division_identity_used_by_the_kernels():
+    """The kernels decode slot ranks with q = int((n + 0.5f) * (1.0f / d)) in float32 instead of an
+    integer division.  The identity q == n // d is checked here at every multiple of d and its
+    neighbours (where a rounding error would show first) for all divisors a tile can have."""
+    for d in list(range(1, 2049)) + list(range(2049, 32769, 97)) + [32768]:
+        inv = np.float32(1.0) / np.float32(d)
+        k = np.arange(0, (1 << 17) // d + 2, dtype=np.int64)
+        n = np.unique(np.clip(np.concatenate([k * d - 1, k * d, k * d + 1, k * d + d // 2]), 0, (1 << 17) - 1))
+        q = ((n.astype(np.float32) + np.float32(0.5)) * inv).astype(np.int64)
+        assert np.array_equal(q, n // d), d
