@@ -75,9 +75,11 @@ __device__ __forceinline__ float load_uniform(const float* p, size_t i) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// two floats -> two bf16 (round to nearest even) in one dword; gfx950 converts in hardware
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v2f{lo, hi}, v2bf));
 }
 
 // Work item of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs by the hardware;
@@ -146,18 +148,18 @@ __device__ __forceinline__ void store_rows(const AttnArgs& a, int bh, int u, int
                 *reinterpret_cast<v4f*>(wave_lds + n * pitch + col * 4) = o;
             } else {
                 uint2 pk;
-                pk.x = f32_to_bf16_bits(o[0]) | (f32_to_bf16_bits(o[1]) << 16);
-                pk.y = f32_to_bf16_bits(o[2]) | (f32_to_bf16_bits(o[3]) << 16);
+                pk.x = pack_bf16x2(o[0], o[1]);
+                pk.y = pack_bf16x2(o[2], o[3]);
                 *reinterpret_cast<uint2*>(wave_lds + n * pitch + col * 2) = pk;
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         // whole rows: 16 lanes (bf16) or 32 lanes (fp32) per row, 16 bytes per lane
-        const int lanes_per_row = row_bytes / 16;
-        const int rows_per_pass = 64 / lanes_per_row;
+        const int lanes_shift = a.out_f32 ? 5 : 4;
+        const int rows_per_pass = 64 >> lanes_shift;
         for (int r0 = 0; r0 < 16; r0 += rows_per_pass) {
-            const int r = r0 + lane / lanes_per_row, chunk = lane % lanes_per_row;
+            const int r = r0 + (lane >> lanes_shift), chunk = lane & ((1 << lanes_shift) - 1);
             const int in_block = wave * 32 + qb * 16 + r;       // BS: block size
             int rt = 0, rh = 0, rw = 0;
             const bool valid = sub_slot_coords(G, so, slot0 + in_block, &rt, &rh, &rw) &&
