@@ -39,7 +39,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="wan14b-720p")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense BF16 / dense FP8 reference runs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the timed CPU oracle sample")
@@ -114,6 +114,25 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     seg = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(2)] for e in all_events])
     quant_ms, attn_ms = (float(x) for x in seg.mean(axis=0))
+    quant_med, attn_med = (float(x) for x in np.median(seg, axis=0))
+
+    # FLOPs on real tokens only: 4 d * (real query tokens of u) * (real key tokens of v) per kept pair
+    mask, _ = fps.tile_mask_host(shape, w.window)
+    per_axis = [np.minimum(t, g - np.arange(-(-g // t)) * t) for g, t in zip(w.grid, w.tile)]
+    real = (per_axis[0][:, None, None] * per_axis[1][None, :, None] * per_axis[2][None, None, :]).reshape(-1)
+    useful_flop = 4.0 * w.head_dim * w.heads * float(real.astype(np.float64) @ mask.astype(np.float64) @ real.astype(np.float64))
+
+    # the matrix rate the chip sustains on the attention kernel's own instruction (nothing else running)
+    sink = torch.empty(4096 * 256, dtype=torch.float32, device=dev)
+    fps.debug_mfma_rate(4096, 2000, sink)
+    torch.cuda.synchronize()
+    m0, m1 = ev(), ev()
+    m0.record()
+    mfma_flop = fps.debug_mfma_rate(4096, 2000, sink)
+    m1.record()
+    torch.cuda.synchronize()
+    mfma_sustained = mfma_flop / (m0.elapsed_time(m1) * 1e-3) / 1e12
+    del sink
 
     result = {
         "metric": "effective TFLOP/s + ms/call, FP8 3D sliding-tile attention, Wan-14B 720p shape",
@@ -126,7 +145,11 @@ def main():
                    "tile": list(w.tile), "window_tiles": list(w.window), "kept_tile_pairs": pairs,
                    "tflop_per_call": flop / 1e12, "input_gen_s": round(gen_s, 1)},
         "breakdown_ms": {"tile_order_quantize_x3": quant_ms, "attention_raster_out": attn_ms},
+        "breakdown_median_ms": {"tile_order_quantize_x3": quant_med, "attention_raster_out": attn_med},
         "attention_tflops": flop / (attn_ms * 1e-3) / 1e12,
+        "attention_tflops_real_tokens_only": useful_flop / (attn_ms * 1e-3) / 1e12,
+        "mfma_only_sustained_tflops": mfma_sustained,
+        "attention_frac_of_sustained_mfma": flop / (attn_ms * 1e-3) / 1e12 / mfma_sustained,
         "quantize_GBps": 3.0 * 3 * w.heads * L * 128 / (quant_ms * 1e-3) / 1e9,
         "roofline": {"bound": "mfma", "kernel": "attn_fp8_kernel", "achieved": flop / (attn_ms * 1e-3) / 1e12,
                      "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -353,8 +376,10 @@ def cpu_baseline(w, n_heads, TS):
     secs = time.perf_counter() - t0
     sample_pairs = int(fo.tile_mask(g, w.window).sum()) * len(heads)
     sflop = sample_pairs * 4.0 * TS * TS * w.head_dim
+    total_pairs = int(fo.tile_mask(g, w.window).sum()) * w.heads
     return {"value": sflop / secs / 1e12, "unit": "TFLOP/s (computed tile pairs)", "cores": threads,
-            "kind": "oracle", "seconds": secs,
+            "kind": "oracle", "seconds": secs, "sample_tile_pairs": sample_pairs,
+            "extrapolated_full_call_seconds": secs * total_pairs / sample_pairs,
             "sample": f"{len(heads)} of {w.heads} heads of {w.name}, each complete: tile order + quantise all "
                       f"{g.M} tiles of Q,K,V + attention for all {g.M} query tiles ({sample_pairs} tile "
                       f"pairs); BLAS threads = cores, elementwise NumPy is single-threaded"}

@@ -185,6 +185,14 @@ int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,
  * the profiler's FETCH_SIZE / WRITE_SIZE counters. */
 int fps_debug_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Debug: a kernel that does nothing but issue the FP8 matrix instruction of the attention kernel
+ * (v_mfma_f32_16x16x128_f8f6f4, 8 independent accumulator chains per wave, no memory traffic in
+ * the loop): `workgroups` workgroups of 256 threads, `iters` loop trips of 8 instructions per
+ * wave.  FLOPs launched = workgroups * 4 waves * iters * 8 * 65536.  Timed by the caller, it gives
+ * the matrix rate the chip sustains, the yardstick next to the datasheet peak.  `sink` is device
+ * memory of workgroups*256 floats that receives one value per thread. */
+int fps_debug_mfma_rate(int workgroups, int iters, float* sink, void* stream);
+
 /* Debug: the raw score accumulators sum_c qcode_ic * kcode_jc (before the s^Q s^K / sqrt(d)
  * dequantisation of Eq. 3) of query tile u and key tile v of head bh, computed with the same
  * matrix instruction as fps_attn_fwd; `scores` is device memory of TSP*TSP floats, [query][key]

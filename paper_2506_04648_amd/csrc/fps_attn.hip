@@ -872,6 +872,30 @@ __global__ __launch_bounds__(BS * 2) void scores_fp8_kernel(const uint8_t* __res
     }
 }
 
+// MFMA-only loop: 8 independent accumulator chains of the attention kernel's matrix instruction.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ sink, int iters, int x) {
+    v8i a = {x, x, x, x, x, x, x, x};
+    v8i b = a;
+    v4f c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            c[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c[i], 0, 0, 0, 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += c[i][0] + c[i][1] + c[i][2] + c[i][3];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+int launch_mfma_rate(int workgroups, int iters, float* sink, hipStream_t st) {
+    mfma_rate_kernel<<<workgroups, 256, 0, st>>>(sink, iters, 0x38383838);   // E4M3 code of 1.0 in every byte
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? FPS_OK : hip_fail(e, "mfma rate launch");
+}
+
 int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int v, float* out,
                       hipStream_t st) {
     // every (query block, key block) pair of the tile pair; out is [TSP][TSP], query-major

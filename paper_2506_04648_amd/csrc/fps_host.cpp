@@ -297,6 +297,15 @@ int fps_debug_copy(const void* src, void* dst, size_t bytes, void* stream) {
     return launch_copy(src, dst, (long long)bytes, (hipStream_t)stream);
 }
 
+int fps_debug_mfma_rate(int workgroups, int iters, float* sink, void* stream) {
+    FPS_TRY(check_ptr(sink, "sink"));
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24)) {
+        set_error("workgroups must be in 1..2^20 and iters in 1..2^24");
+        return FPS_ERR_INVALID_ARG;
+    }
+    return launch_mfma_rate(workgroups, iters, sink, (hipStream_t)stream);
+}
+
 int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u, int v,
                         float* scores, void* stream) {
     Geom g;

@@ -29,7 +29,7 @@ EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_num_gr
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
            "fps_quantize_raster",
            "fps_pack_tiles_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
-           "fps_debug_scores_block_q8",
+           "fps_debug_scores_block_q8", "fps_debug_mfma_rate",
            "fps_attn_fwd")
 
 
@@ -93,6 +93,7 @@ def lib():
         L.fps_debug_scores_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, vp, vp]
         L.fps_debug_scores_block_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, ip, ip, vp,
                                                 ctypes.POINTER(ctypes.c_int), vp]
+        L.fps_debug_mfma_rate.argtypes = [ip, ip, vp, vp]
         L.fps_attn_fwd.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), ip,
                                    ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, ip, vp, vp]
         for name in EXPORTS:
@@ -262,6 +263,13 @@ def debug_copy(src, dst):
     assert nbytes == dst.numel() * dst.element_size()
     _check(lib().fps_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream()))
     return dst
+
+
+def debug_mfma_rate(workgroups, iters, sink):
+    """Launch the MFMA-only kernel; returns the FLOPs it executes (the caller times it)."""
+    assert sink.is_cuda and sink.numel() >= workgroups * 256
+    _check(lib().fps_debug_mfma_rate(workgroups, iters, _ptr(sink), _stream()))
+    return workgroups * 4 * iters * 8 * 65536.0
 
 
 def debug_scores_q8(shape: Shape, q8, k8, bh, u, v):

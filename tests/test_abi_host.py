@@ -145,6 +145,9 @@ def test_device_entry_points_validate_before_launching():
     assert L.fps_attn_fwd(S, ctypes.byref(win), 1, None, good, good, good, good, good, good, 0,
                           good, 1, 2, None, None) == fps.FPS_ERR_INVALID_ARG   # bad output layout
     assert L.fps_quantize_raster(S, good, 0, 0, None, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_debug_mfma_rate(0, 4, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_debug_mfma_rate(4, 0, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_debug_mfma_rate(4, 4, None, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_copy(good, good, 24, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_copy(good, None, 32, None) == fps.FPS_ERR_INVALID_ARG
     big = fps.make_shape(2, (64, 64, 64), (64, 32, 32))                         # 65536-token tiles

@@ -429,6 +429,20 @@ def test_random_configurations(seed):
     gu.assert_parity(st, f"random case {seed}: {grid} {tile} {qtile} {window} {prec} {vscale}")
 
 
+def test_mfma_rate_kernel_runs():
+    """The MFMA-only micro-benchmark kernel (yardstick of the roofline): every thread writes one
+    finite value, and a thread's value grows linearly with the trip count (accumulator chains)."""
+    import torch
+    say("mfma rate")
+    a = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
+    b = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
+    assert fps.debug_mfma_rate(8, 4, a) == 8 * 4 * 4 * 8 * 65536.0
+    fps.debug_mfma_rate(8, 8, b)
+    torch.cuda.synchronize()
+    assert torch.isfinite(a).all() and torch.isfinite(b).all() and (a != 0).all()
+    assert torch.equal(b, 2 * a)
+
+
 def test_batch_and_heads_are_interchangeable():
     """Tensors are indexed by b*heads + h: (B=2, heads=3) equals (B=1, heads=6) bit for bit."""
     import torch
