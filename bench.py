@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--variants", action="store_true",
                     help="also time the variants of the path on the same grid: per-channel V scales, BF16 with "
                          "the sparse window, the shifted-window edge rule, other tile shapes")
+    ap.add_argument("--window-ablation", action="store_true",
+                    help="also time the window sizes of the paper's window ablation (Table 4) on the "
+                         "Wan2.1-1.3B 480p grid, against the dense BF16 kernel on the same grid")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads are independent and would shard across "
@@ -194,6 +197,9 @@ def main():
     if args.variants:
         result["variants"] = run_variants(w, raster, dev)
 
+    if args.window_ablation:
+        result["window_ablation"] = run_window_ablation(dev)
+
     if args.schedule:
         del raster
         result["schedule"] = run_schedule(w, shape, dev)
@@ -285,6 +291,59 @@ def run_variants(w, raster, dev, reps=5):
             fp8_case("tile (3,4,4): 48 tokens in two 32-slot blocks", (3, 4, 4), (1, 7, 13)),
             fp8_case("tile (12,16,16): 3072 tokens, 24 blocks", (12, 16, 16), (1, 1, 3))]
     return rows
+
+
+def run_window_ablation(dev, reps=10):
+    """The window sizes (t,h,w) of the paper's window ablation (Table 4, Wan2.1-1.3B; kernel
+    speed-ups 3.24x / 3.07x / 1.69x / 5.16x over BF16 on H20, tile not stated) on the 480p grid with
+    the (6,8,8) tile the paper calls hardware-friendly and with the (1,8,16) tile of the other
+    workloads: FP8 attention ms per call and the speed-up over this build's dense BF16 kernel."""
+    import torch
+    from paper_2506_04648_amd import fps, synth
+    w = synth.WAN_1_3B_480P
+    q, k, v = synth.qkv_raster(w, workers=min(16, os.cpu_count() or 1))
+    raster = [torch.from_numpy(a[None]).to(dev).to(torch.bfloat16) for a in (q, k, v)]
+    del q, k, v
+    out = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.bfloat16, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    rows = []
+    for tile in ((6, 8, 8), (1, 8, 16)):
+        shape = fps.make_shape(w.heads, w.grid, tile)
+        M = fps.num_tiles(shape)
+        tiled = torch.empty((1, w.heads, M * fps.tile_slots(shape), 128), dtype=torch.bfloat16, device=dev)
+        p16 = []
+        for i in range(3):
+            fps.tile_order(shape, raster[i], out=tiled)
+            p16.append(fps.pack_tiles_bf16(shape, tiled, i))
+        dense_win = tuple(2 * (-(-g // t)) - 1 for g, t in zip(w.grid, tile))
+        dense_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_BF16, p16[0][0], p16[1][0], p16[2][0],
+                                              sv=p16[2][1], out=out, raster_out=True))
+        del p16, tiled
+        q8 = [fps.quantize_tiles(shape, raster[i], i, raster=True) for i in range(3)]
+        quant_ms = timed(lambda: [fps.quantize_tiles(shape, raster[i], i, out=q8[i][0], scales=q8[i][1], raster=True)
+                                  for i in range(3)])
+        for window in ((3, 3, 1), (5, 6, 10), (6, 6, 6), (6, 6, 1)):
+            ms = timed(lambda: fps.attn_fwd(shape, window, fps.PREC_FP8, q8[0][0], q8[1][0], q8[2][0],
+                                            q8[0][1], q8[1][1], q8[2][1], out=out, raster_out=True))
+            _, pairs = fps.tile_mask_host(shape, window)
+            rows.append({"tile": list(tile), "window": list(window), "kept_tile_pairs": pairs, "of_pairs": M * M,
+                         "fp8_attention_ms": ms, "quantize_x3_ms": quant_ms, "dense_bf16_ms": dense_ms,
+                         "speedup_attention_only": dense_ms / ms, "speedup_with_quantize": dense_ms / (ms + quant_ms)})
+        del q8
+    return {"workload": w.name, "paper_speedups_H20": {"3,3,1": 3.24, "5,6,10": 3.07, "6,6,6": 1.69, "6,6,1": 5.16},
+            "rows": rows}
 
 
 def run_schedule(w, shape, dev, num_steps=50, alpha1=0.2, alpha2=0.5):
