@@ -178,10 +178,8 @@ def main():
             torch.cuda.synchronize()
             return a.elapsed_time(b) / reps
 
-        tiled = [fps.tile_order(shape, r) for r in raster]
         out_tiled = torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev)
-        p16 = [fps.pack_tiles_bf16(shape, tiled[i], i) for i in range(3)]
-        del tiled
+        p16 = [fps.pack_tiles_bf16(shape, raster[i], i, raster=True) for i in range(3)]
         bf16_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_BF16, p16[0][0], p16[1][0], p16[2][0],
                                              sv=p16[2][1], out=out_tiled), 2)
         del p16
@@ -255,15 +253,12 @@ def run_variants(w, raster, dev, reps=5):
     def bf16_case(name, tile, window):
         shape = fps.make_shape(w.heads, w.grid, tile)
         M = fps.num_tiles(shape)
-        L = M * fps.tile_slots(shape)
-        tiled = torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev)
         packed = [torch.empty(fps.packed_bytes(shape, fps.PREC_BF16), dtype=torch.uint8, device=dev) for _ in range(3)]
         vs = torch.empty((1, w.heads, M), dtype=torch.float32, device=dev)
 
         def prep():
             for i in range(3):
-                fps.tile_order(shape, raster[i], out=tiled)
-                fps.pack_tiles_bf16(shape, tiled, i, out=packed[i], vscale=vs)
+                fps.pack_tiles_bf16(shape, raster[i], i, out=packed[i], vscale=vs, raster=True)
 
         def attn():
             fps.attn_fwd(shape, window, fps.PREC_BF16, packed[0], packed[1], packed[2], sv=vs, out=out,
@@ -322,15 +317,11 @@ def run_window_ablation(dev, reps=10):
     for tile in ((6, 8, 8), (1, 8, 16)):
         shape = fps.make_shape(w.heads, w.grid, tile)
         M = fps.num_tiles(shape)
-        tiled = torch.empty((1, w.heads, M * fps.tile_slots(shape), 128), dtype=torch.bfloat16, device=dev)
-        p16 = []
-        for i in range(3):
-            fps.tile_order(shape, raster[i], out=tiled)
-            p16.append(fps.pack_tiles_bf16(shape, tiled, i))
+        p16 = [fps.pack_tiles_bf16(shape, raster[i], i, raster=True) for i in range(3)]
         dense_win = tuple(2 * (-(-g // t)) - 1 for g, t in zip(w.grid, tile))
         dense_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_BF16, p16[0][0], p16[1][0], p16[2][0],
                                               sv=p16[2][1], out=out, raster_out=True))
-        del p16, tiled
+        del p16
         q8 = [fps.quantize_tiles(shape, raster[i], i, raster=True) for i in range(3)]
         quant_ms = timed(lambda: [fps.quantize_tiles(shape, raster[i], i, out=q8[i][0], scales=q8[i][1], raster=True)
                                   for i in range(3)])
@@ -351,7 +342,7 @@ def run_schedule(w, shape, dev, num_steps=50, alpha1=0.2, alpha2=0.5):
     1-10 dense BF16, 11-25 FP8 with a 7x5x5-tile window, 26-50 FP8 with a 3x3x3-tile window, every
     call on its own seed-generated Q, K, V (all 50 sets resident in HBM before the clock starts).
     Each call runs the whole path for its regime: FP8 = fused tile-order+quantise x3 + attention;
-    BF16 = tile order x3 + operand packing x3 + attention.  The regime is picked by the library from
+    BF16 = fused tile-order+operand packing x3 + attention.  The regime is picked by the library from
     the step configuration passed to fps_attn_fwd."""
     import torch
     from paper_2506_04648_amd import fps, synth
@@ -369,7 +360,6 @@ def run_schedule(w, shape, dev, num_steps=50, alpha1=0.2, alpha2=0.5):
     L = M * fps.tile_slots(shape)
     packed8 = [torch.empty(fps.packed_bytes(shape, fps.PREC_FP8), dtype=torch.uint8, device=dev) for _ in range(3)]
     packed16 = [torch.empty(fps.packed_bytes(shape, fps.PREC_BF16), dtype=torch.uint8, device=dev) for _ in range(3)]
-    tiled = [torch.empty((1, w.heads, L, 128), dtype=torch.bfloat16, device=dev) for _ in range(3)]
     scales = [torch.empty((1, w.heads, M), dtype=torch.float32, device=dev) for _ in range(3)]
     out = torch.empty((1, w.heads) + tuple(w.grid) + (128,), dtype=torch.bfloat16, device=dev)
 
@@ -384,8 +374,7 @@ def run_schedule(w, shape, dev, num_steps=50, alpha1=0.2, alpha2=0.5):
                          scales[2], out=out, raster_out=True, step=cfg)
         else:
             for i in range(3):
-                fps.tile_order(shape, x[i], out=tiled[i])
-                fps.pack_tiles_bf16(shape, tiled[i], i, out=packed16[i], vscale=scales[2])
+                fps.pack_tiles_bf16(shape, x[i], i, out=packed16[i], vscale=scales[2], raster=True)
             fps.attn_fwd(shape, None, prec, packed16[0], packed16[1], packed16[2], sv=scales[2], out=out,
                          raster_out=True, step=cfg)
         return prec

@@ -176,6 +176,12 @@ int fps_quantize_raster(const fps_shape* shape, const void* x_raster_bf16, fps_r
 int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_role role,
                         void* xp_out, float* vscale_out, void* stream);
 
+/* fps_tile_order fused into fps_pack_tiles_bf16: the input is the RASTER bf16 tensor
+ * [B,heads,T,H,W,128] (device).  Outputs are bit-identical to fps_tile_order followed by
+ * fps_pack_tiles_bf16. */
+int fps_pack_raster_bf16(const fps_shape* shape, const void* x_raster_bf16, fps_role role,
+                         void* xp_out, float* vscale_out, void* stream);
+
 /* Debug: packed E4M3 tensor (device) -> plain row-major codes [B,heads,M*TSP,128] (device). */
 int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,
                         uint8_t* codes_rowmajor, void* stream);

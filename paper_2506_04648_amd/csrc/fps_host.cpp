@@ -274,7 +274,18 @@ int fps_pack_tiles_bf16(const fps_shape* shape, const void* x_tiled_bf16, fps_ro
     FPS_TRY(check_ptr(x_tiled_bf16, "x_tiled_bf16"));
     FPS_TRY(check_ptr(xp_out, "xp_out"));
     if (role == FPS_ROLE_V) FPS_TRY(check_ptr(vscale_out, "vscale_out"));
-    return launch_pack_bf16(g, x_tiled_bf16, role, xp_out, vscale_out, (hipStream_t)stream);
+    return launch_pack_bf16(g, x_tiled_bf16, 0, role, xp_out, vscale_out, (hipStream_t)stream);
+}
+
+int fps_pack_raster_bf16(const fps_shape* shape, const void* x_raster_bf16, fps_role role,
+                         void* xp_out, float* vscale_out, void* stream) {
+    Geom g;
+    FPS_TRY(check_shape(shape, &g));
+    FPS_TRY(check_enum(role, FPS_ROLE_V, "role"));
+    FPS_TRY(check_ptr(x_raster_bf16, "x_raster_bf16"));
+    FPS_TRY(check_ptr(xp_out, "xp_out"));
+    if (role == FPS_ROLE_V) FPS_TRY(check_ptr(vscale_out, "vscale_out"));
+    return launch_pack_bf16(g, x_raster_bf16, 1, role, xp_out, vscale_out, (hipStream_t)stream);
 }
 
 int fps_debug_unpack_q8(const fps_shape* shape, const void* xq, fps_role role,

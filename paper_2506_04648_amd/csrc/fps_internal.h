@@ -91,7 +91,8 @@ int launch_tile_order(const Geom& g, const void* in, void* out, hipStream_t st);
 int launch_tile_unorder(const Geom& g, const void* in, int elem_bytes, void* out, hipStream_t st);
 int launch_quantize(const Geom& g, const void* x, int raster, int role, int vscale, void* xq,
                     float* scales, hipStream_t st);
-int launch_pack_bf16(const Geom& g, const void* x, int role, void* xp, float* vscale, hipStream_t st);
+int launch_pack_bf16(const Geom& g, const void* x, int raster, int role, void* xp, float* vscale,
+                     hipStream_t st);
 int launch_unpack_q8(const Geom& g, const void* xq, int role, uint8_t* out, hipStream_t st);
 int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, const void* k,
                 const void* v, const float* sq, const float* sk, const float* sv, int vscale,

@@ -72,7 +72,9 @@ __global__ void tile_unorder_kernel(const uint4* __restrict__ in, uint4* __restr
 // amax * 2^-e in [2^14, 2^15), which keeps every bf16 value exact unless it is more than 2^28
 // times smaller than the tile's largest one, and vscale[tile] = 2^e undoes it in the kernel.
 // For tiles of several blocks the tile amax is computed beforehand (tile_amax != nullptr).
-template <int BS>
+// RASTER: `in` is the raster tensor and the block's tokens are gathered from it (padding slots read
+// as zero), which fuses the tile ordering into this pass.
+template <int BS, bool RASTER>
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict__ in,
                                                         uint4* __restrict__ out,
                                                         float* __restrict__ vscale, int role, Geom g,
@@ -80,25 +82,29 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
     __shared__ uint16_t tile[BS * 128];
     __shared__ uint32_t red[4];
     const long long blk = blockIdx.x;
-    const uint4* src = in + blk * (BS * 16);
     uint4* dst = out + blk * (BS * 16);
     constexpr int kChunks = BS * 16;
+    const BlockOrigin org = block_origin(g, blockIdx.x);
+    auto load = [&](int c) {                               // chunk c = 8 channels (c & 15) of slot c >> 4
+        const uint4* row = token_row<RASTER>(in, g, org, blockIdx.x, c >> 4);
+        return row ? row[c & 15] : make_uint4(0, 0, 0, 0);
+    };
     if (role == FPS_ROLE_Q) {
-        for (int c = threadIdx.x; c < kChunks; c += 256) dst[c] = src[c];
+        for (int c = threadIdx.x; c < kChunks; c += 256) dst[c] = load(c);
         return;
     }
     if (role == FPS_ROLE_K) {
         for (int c = threadIdx.x; c < kChunks; c += 256) {
             const int j = c >> 4, c8 = c & 15;             // row, 8-channel chunk
             const int b = j >> 4, n = j & 15, ks = c8 >> 2, gg = c8 & 3;
-            dst[(b * 4 + ks) * 64 + gg * 16 + n] = src[c];
+            dst[(b * 4 + ks) * 64 + gg * 16 + n] = load(c);
         }
         return;
     }
     uint4* t4 = reinterpret_cast<uint4*>(tile);
     uint32_t mb = 0;
     for (int c = threadIdx.x; c < kChunks; c += 256) {
-        const uint4 v = src[c];
+        const uint4 v = load(c);
         t4[c] = v;
         mb = amax_bits16(v, mb);
     }
@@ -181,16 +187,25 @@ int launch_copy(const void* in, void* out, long long bytes, hipStream_t st) {
     return e == hipSuccess ? FPS_OK : hip_fail(e, "copy launch");
 }
 
-int launch_pack_bf16(const Geom& g, const void* x, int role, void* xp, float* vscale, hipStream_t st) {
+int launch_pack_bf16(const Geom& g, const void* x, int raster, int role, void* xp, float* vscale,
+                     hipStream_t st) {
     const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M * g.NS;   // ntiles: quantisation groups
     const float* tile_amax = nullptr;
     if (role == FPS_ROLE_V && g.KBS > 1) {                  // `vscale` holds the tile amax meanwhile
         clear_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>((uint32_t*)vscale, ntiles);
-        block_amax_kernel<false><<<blocks, 256, 0, st>>>((const uint4*)x, (uint32_t*)vscale, g);
+        if (raster) block_amax_kernel<true><<<blocks, 256, 0, st>>>((const uint4*)x, (uint32_t*)vscale, g);
+        else        block_amax_kernel<false><<<blocks, 256, 0, st>>>((const uint4*)x, (uint32_t*)vscale, g);
         tile_amax = vscale;
     }
-    if (g.BS == 128) pack_bf16_kernel<128><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role, g, tile_amax);
-    else             pack_bf16_kernel<32><<<blocks, 256, 0, st>>>((const uint4*)x, (uint4*)xp, vscale, role, g, tile_amax);
+    const uint4* xi = (const uint4*)x;
+    uint4* xo = (uint4*)xp;
+    if (g.BS == 128) {
+        if (raster) pack_bf16_kernel<128, true><<<blocks, 256, 0, st>>>(xi, xo, vscale, role, g, tile_amax);
+        else        pack_bf16_kernel<128, false><<<blocks, 256, 0, st>>>(xi, xo, vscale, role, g, tile_amax);
+    } else {
+        if (raster) pack_bf16_kernel<32, true><<<blocks, 256, 0, st>>>(xi, xo, vscale, role, g, tile_amax);
+        else        pack_bf16_kernel<32, false><<<blocks, 256, 0, st>>>(xi, xo, vscale, role, g, tile_amax);
+    }
     if (tile_amax) amax_to_pow2_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>(vscale, ntiles);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "pack_bf16 launch");

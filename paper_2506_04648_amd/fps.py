@@ -28,7 +28,7 @@ EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_num_gr
            "fps_packed_bytes",
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
            "fps_quantize_raster",
-           "fps_pack_tiles_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
+           "fps_pack_tiles_bf16", "fps_pack_raster_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
            "fps_debug_scores_block_q8", "fps_debug_mfma_rate",
            "fps_attn_fwd")
 
@@ -88,6 +88,7 @@ def lib():
         L.fps_quantize_tiles.argtypes = [ctypes.POINTER(Shape), vp, ip, ip, vp, vp, vp]
         L.fps_quantize_raster.argtypes = [ctypes.POINTER(Shape), vp, ip, ip, vp, vp, vp]
         L.fps_pack_tiles_bf16.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp, vp]
+        L.fps_pack_raster_bf16.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp, vp]
         L.fps_debug_unpack_q8.argtypes = [ctypes.POINTER(Shape), vp, ip, vp, vp]
         L.fps_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fps_debug_scores_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, vp, vp]
@@ -235,8 +236,9 @@ def quantize_tiles(shape: Shape, x_tiled, role, vscale=VSCALE_TILE, out=None, sc
     return out, scales
 
 
-def pack_tiles_bf16(shape: Shape, x_tiled, role, out=None, vscale=None):
-    """Returns (packed tensor, per-tile V scales or None)."""
+def pack_tiles_bf16(shape: Shape, x_tiled, role, out=None, vscale=None, raster=False):
+    """BF16-mode operand packing of a tile-ordered tensor, or (raster=True) of a raster tensor with
+    the tile ordering fused in.  Returns (packed tensor, per-group V scales or None)."""
     import torch
     assert x_tiled.dtype == torch.bfloat16 and x_tiled.is_cuda and x_tiled.is_contiguous()
     if out is None:
@@ -244,8 +246,8 @@ def pack_tiles_bf16(shape: Shape, x_tiled, role, out=None, vscale=None):
     if role == ROLE_V and vscale is None:
         vscale = torch.empty((shape.B, shape.heads, num_groups(shape)), dtype=torch.float32,
                              device=x_tiled.device)
-    _check(lib().fps_pack_tiles_bf16(ctypes.byref(shape), _ptr(x_tiled), role, _ptr(out),
-                                     _ptr(vscale), _stream()))
+    fn = lib().fps_pack_raster_bf16 if raster else lib().fps_pack_tiles_bf16
+    _check(fn(ctypes.byref(shape), _ptr(x_tiled), role, _ptr(out), _ptr(vscale), _stream()))
     return out, vscale
 
 

@@ -113,9 +113,13 @@ def test_quantisation_sub_tiles_layout_and_codes_bit_exact(grid, tile, qtile):
         assert np.array_equal(fps.tile_unorder(run.shape, t)[0].float().cpu().numpy(), a)
     assert run.quantize()[0][1].shape[-1] == run.g.n_groups
     _check_quantize(run, range(2), f"sub-tile {tile} {qtile}")
-    for role in range(3):                                   # fused raster entry == tiled entry
+    p16 = run.pack_bf16()
+    for role in range(3):                                   # fused raster entries == tiled entries
         xq, sc = fps.quantize_tiles(run.shape, run.raster[role], role, raster=True)
         assert torch.equal(xq, run.q8[role][0]) and torch.equal(sc, run.q8[role][1])
+        xp, vs = fps.pack_tiles_bf16(run.shape, run.raster[role], role, raster=True)
+        assert torch.equal(xp, p16[role][0])
+        assert (vs is None and p16[role][1] is None) or torch.equal(vs, p16[role][1])
 
 
 @pytest.mark.parametrize("prec", [fps.PREC_FP8, fps.PREC_BF16])
@@ -370,6 +374,11 @@ def test_fused_raster_entry_points_match_the_unfused_path(grid, tile):
     for role in range(3):
         xq, sc = fps.quantize_tiles(run.shape, run.raster[role], role, raster=True)
         assert torch.equal(xq, q8[role][0]) and torch.equal(sc, q8[role][1])
+    p16 = run.pack_bf16()
+    for role in range(3):
+        xp, vs = fps.pack_tiles_bf16(run.shape, run.raster[role], role, raster=True)
+        assert torch.equal(xp, p16[role][0])
+        assert (vs is None and p16[role][1] is None) or torch.equal(vs, p16[role][1])
     for prec in (fps.PREC_FP8, fps.PREC_BF16):
         for dt in (torch.float32, torch.bfloat16):
             tiled = run.attn(prec, out_dtype=dt)
