@@ -100,12 +100,13 @@ __device__ __forceinline__ void write_v_block(const uint8_t* stage, uint4* dst, 
     }
 }
 
-// One workgroup of 256 threads per block of BS slots.  A scale group of one block (KBS = 1) is
-// handled in a single pass: amax, scale, encode.  For larger groups the amax comes from block_amax_kernel
-// (tile_amax != nullptr) and this kernel only encodes.
+// One workgroup of 256 threads per NB consecutive blocks of BS slots.  A scale group of up to three
+// blocks is handled by one workgroup in a single pass over HBM (NB = blocks per group): all its
+// blocks are held in registers while the amax is reduced, then encoded.  Larger groups take their
+// amax from block_amax_kernel (tile_amax != nullptr, NB = 1) and this kernel only encodes.
 // RASTER: x is the raster tensor [BH,T,H,W,128] and the block's tokens are gathered from it (padded
 // slots read as zero), which fuses the tile ordering of Sec. 3.2 step (1) into this pass.
-template <int BS, bool RASTER>
+template <int BS, bool RASTER, int NB>
 __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __restrict__ x,
                                                              uint8_t* __restrict__ xq,
                                                              float* __restrict__ scales, int role,
@@ -113,51 +114,59 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __rest
     constexpr int U = BS / 32;                      // 32-byte units (16 channels of one token) per thread
     __shared__ uint32_t red[4];
     __shared__ __attribute__((aligned(16))) uint8_t stage[BS * 128];
-    const long long blk = blockIdx.x;
-    uint4* dst = reinterpret_cast<uint4*>(xq + blk * (BS * 128));
+    const int first = blockIdx.x * NB;              // first block of this workgroup
     const int tid = threadIdx.x;
 
-    uint4 lo[U], hi[U];
+    uint4 lo[NB][U], hi[NB][U];
     uint32_t mb = 0;
-    const BlockOrigin org = block_origin(g, blockIdx.x);
 #pragma unroll
-    for (int i = 0; i < U; ++i) {
-        const int unit = tid + 256 * i;              // token = unit >> 3, 16-channel group = unit & 7
-        const uint4* row = token_row<RASTER>(x, g, org, blockIdx.x, unit >> 3);
-        lo[i] = make_uint4(0, 0, 0, 0);
-        hi[i] = lo[i];
-        if (row) { lo[i] = row[2 * (unit & 7)]; hi[i] = row[2 * (unit & 7) + 1]; }
-        mb = amax_pairs16(lo[i], mb);
-        mb = amax_pairs16(hi[i], mb);
+    for (int kb = 0; kb < NB; ++kb) {
+        const BlockOrigin org = block_origin(g, first + kb);
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            const int unit = tid + 256 * i;          // token = unit >> 3, 16-channel group = unit & 7
+            const uint4* row = token_row<RASTER>(x, g, org, first + kb, unit >> 3);
+            lo[kb][i] = make_uint4(0, 0, 0, 0);
+            hi[kb][i] = lo[kb][i];
+            if (row) { lo[kb][i] = row[2 * (unit & 7)]; hi[kb][i] = row[2 * (unit & 7) + 1]; }
+            mb = amax_pairs16(lo[kb][i], mb);
+            mb = amax_pairs16(hi[kb][i], mb);
+        }
     }
     mb = amax_of_pairs(mb);
     float amax;
     if (tile_amax) {
-        amax = tile_amax[blk / g.KBS];
+        amax = tile_amax[first / g.KBS];
     } else {
         mb = block_max_256(mb, red);
         amax = __uint_as_float(mb << 16);
     }
     const float s = (amax == 0.0f) ? 1.0f : amax / 448.0f;   // Eq. 4 (correctly rounded division)
-    if (!tile_amax && tid == 0) scales[blk] = s;
+    if (!tile_amax && tid == 0) scales[blockIdx.x] = s;       // the workgroup is the whole group
 
 #pragma unroll
-    for (int i = 0; i < U; ++i) {
-        const int unit = tid + 256 * i;
-        const uint4 codes = encode16(lo[i], hi[i], s);
-        const int j = unit >> 3, c16 = unit & 7;
-        if (role == FPS_ROLE_Q) {
-            dst[unit] = codes;
-        } else if (role == FPS_ROLE_K) {
-            const int b = j >> 4, n = j & 15, gg = c16 >> 1, h = c16 & 1;
-            dst[(b * 2 + h) * 64 + gg * 16 + n] = codes;
-        } else {
-            reinterpret_cast<uint4*>(stage)[unit] = codes;
+    for (int kb = 0; kb < NB; ++kb) {
+        uint4* dst = reinterpret_cast<uint4*>(xq + (long long)(first + kb) * (BS * 128));
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            const int unit = tid + 256 * i;
+            const uint4 codes = encode16(lo[kb][i], hi[kb][i], s);
+            const int j = unit >> 3, c16 = unit & 7;
+            if (role == FPS_ROLE_Q) {
+                dst[unit] = codes;
+            } else if (role == FPS_ROLE_K) {
+                const int b = j >> 4, n = j & 15, gg = c16 >> 1, h = c16 & 1;
+                dst[(b * 2 + h) * 64 + gg * 16 + n] = codes;
+            } else {
+                reinterpret_cast<uint4*>(stage)[unit] = codes;
+            }
+        }
+        if (role == FPS_ROLE_V) {                    // uniform branch: role is a kernel argument
+            __syncthreads();
+            write_v_block<BS>(stage, dst, tid);
+            if (kb + 1 < NB) __syncthreads();        // the staging buffer is reused by the next block
         }
     }
-    if (role != FPS_ROLE_V) return;
-    __syncthreads();
-    write_v_block<BS>(stage, dst, tid);
 }
 
 // ---- per-channel V (Sec. 3.2, Algorithm 1 step 3): s_c = max over ALL tokens of |V[:,c]| / 448 ----
@@ -251,27 +260,40 @@ static int launch_quantize_channels(const Geom& g, const void* x, int raster, vo
     return e == hipSuccess ? FPS_OK : hip_fail(e, "quantize_channels launch");
 }
 
+template <int BS, int NB>
+static void launch_quantize_nb(const Geom& g, const uint4* xi, int raster, int role, uint8_t* xo, float* scales,
+                               const float* tile_amax, int grid, hipStream_t st) {
+    if (raster) quantize_tiles_kernel<BS, true, NB><<<grid, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
+    else        quantize_tiles_kernel<BS, false, NB><<<grid, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
+}
+
 int launch_quantize(const Geom& g, const void* x, int raster, int role, int vscale, void* xq,
                     float* scales, hipStream_t st) {
     if (vscale != FPS_VSCALE_TILE) return launch_quantize_channels(g, x, raster, xq, scales, st);
-    const int blocks = g.BH * g.M * g.KB, ntiles = g.BH * g.M * g.NS;   // ntiles: quantisation groups
+    const int blocks = g.BH * g.M * g.KB, groups = g.BH * g.M * g.NS;
     const uint4* xi = (const uint4*)x;
     uint8_t* xo = (uint8_t*)xq;
-    const float* tile_amax = nullptr;
-    if (g.KBS > 1) {                    // group amax over several blocks first; `scales` holds it meanwhile
-        clear_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>((uint32_t*)scales, ntiles);
+    if (g.KBS <= 3) {                   // one workgroup per scale group: a single pass over the input
+        if (g.BS == 128) {
+            switch (g.KBS) {
+                case 1: launch_quantize_nb<128, 1>(g, xi, raster, role, xo, scales, nullptr, groups, st); break;
+                case 2: launch_quantize_nb<128, 2>(g, xi, raster, role, xo, scales, nullptr, groups, st); break;
+                default: launch_quantize_nb<128, 3>(g, xi, raster, role, xo, scales, nullptr, groups, st); break;
+            }
+        } else {                        // 32-slot blocks: groups of at most 96 tokens, three blocks
+            switch (g.KBS) {
+                case 1: launch_quantize_nb<32, 1>(g, xi, raster, role, xo, scales, nullptr, groups, st); break;
+                case 2: launch_quantize_nb<32, 2>(g, xi, raster, role, xo, scales, nullptr, groups, st); break;
+                default: launch_quantize_nb<32, 3>(g, xi, raster, role, xo, scales, nullptr, groups, st); break;
+            }
+        }
+    } else {                            // group amax over many blocks first; `scales` holds it meanwhile
+        clear_kernel<<<(groups + 255) / 256, 256, 0, st>>>((uint32_t*)scales, groups);
         if (raster) block_amax_kernel<true><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
         else        block_amax_kernel<false><<<blocks, 256, 0, st>>>(xi, (uint32_t*)scales, g);
-        tile_amax = scales;
+        launch_quantize_nb<128, 1>(g, xi, raster, role, xo, scales, scales, blocks, st);
+        amax_to_scale_kernel<<<(groups + 255) / 256, 256, 0, st>>>(scales, groups);
     }
-    if (g.BS == 128) {
-        if (raster) quantize_tiles_kernel<128, true><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
-        else        quantize_tiles_kernel<128, false><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
-    } else {
-        if (raster) quantize_tiles_kernel<32, true><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
-        else        quantize_tiles_kernel<32, false><<<blocks, 256, 0, st>>>(xi, xo, scales, role, g, tile_amax);
-    }
-    if (g.KBS > 1) amax_to_scale_kernel<<<(ntiles + 255) / 256, 256, 0, st>>>(scales, ntiles);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "quantize_tiles launch");
 }
