@@ -447,6 +447,10 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         const float svv = sv_next;
         if (a.visited && bh == 0 && tid == 0 && jq == 0 && w0.jk == 0) a.visited[(size_t)u * G.M + v] = 1;
         __syncthreads();                 // every wave is past QK(i) and PV(i-2); staged tiles are visible
+        // the first V operand is requested at once: its LDS latency passes under the scalar work
+        // (tile walk, addresses, scale loads) that follows
+        v8i vop[2];
+        if (!FIRST) vop[0] = load_v(vprev, 0);
         // K(i+2) replaces K(i), V(i) goes to its own buffer; the copies are issued between the
         // MFMAs of phase 1 rather than in one burst (the load unit takes them slowly)
         const bool fetch_k = it + 2 < ntiles;
@@ -468,8 +472,6 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
             mx[qb] = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
                                      __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
         v4f tq[2][2];                                      // MFMA results wait one block for their fma
-        v8i vop[2];
-        if (!FIRST) vop[0] = load_v(vprev, 0);
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) {
             if (!FIRST) {
@@ -490,6 +492,8 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         }
         static_assert(2 * CPT <= 8, "staging is spread over the 8 channel blocks of phase 1");
         if (!FIRST) pv_accumulate(7, tq[1], svv_prev);
+        v8i kop[2];                      // K(i+1) has been visible since the barrier: ask for its first
+        if (!LAST) kop[0] = load_k(knxt, 0);   // operand before the cross-lane reduction of the maxima
         float cm[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -505,8 +509,6 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 
         // ---- phase 2: P(i) and its FP8 codes  |  early QK(i+1) ------------------------------
         float rs[2] = {0.f, 0.f};
-        v8i kop[2];
-        if (!LAST) kop[0] = load_k(knxt, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
