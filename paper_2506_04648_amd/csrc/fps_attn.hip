@@ -75,6 +75,24 @@ __device__ __forceinline__ float load_uniform(const float* p, size_t i) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Reductions over the four lanes n, n+16, n+32, n+48 that hold one query row.  gfx950 swaps rows of
+// 16 lanes (and halves of 32) between two registers at VALU speed: with both operands equal to t,
+// v_permlane16_swap leaves (r0,r0,r2,r2) and (r1,r1,r3,r3), v_permlane32_swap (lo,lo) and (hi,hi),
+// so two swaps and two combines replace two LDS-routed shuffles and their latency.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float max_over_row_lanes(float t) {
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    t = __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    return __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_over_row_lanes(float t) {
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    t = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // two floats -> two bf16 (round to nearest even) in one dword; gfx950 converts in hardware
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
@@ -498,8 +516,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             float t = mx[qb];
-            t = __builtin_fmaxf(t, __shfl_xor(t, 16));
-            t = __builtin_fmaxf(t, __shfl_xor(t, 32));
+            t = max_over_row_lanes(t);
             const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(t * sc));
             alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
             m_run[qb] = m_new;
@@ -564,8 +581,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         float l = l_run[qb];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        l = sum_over_row_lanes(l);
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;               // l already carries the factor 448
     }
     __syncthreads();                                       // all waves are done with the staged tiles
@@ -762,8 +778,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             float t = mx[qb];
-            t = __builtin_fmaxf(t, __shfl_xor(t, 16));
-            t = __builtin_fmaxf(t, __shfl_xor(t, 32));
+            t = max_over_row_lanes(t);
             const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(t * sc));
             alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
             m_run[qb] = m_new;
@@ -835,8 +850,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         float l = l_run[qb];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        l = sum_over_row_lanes(l);
         inv[qb] = l > 0.f ? 1.0f / l : 0.f;
     }
     __syncthreads();                                       // all waves are done with the staged tiles
