@@ -298,6 +298,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     constexpr int NB = BS / 16;
     constexpr int NTHR = BS * 2;
     constexpr int CPT = (BS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile
+    constexpr bool K_IN_PHASE2 = CPT <= NB;                // K's staging copies ride in phase 2 when its steps suffice
     constexpr int TILE_BYTES = BS * 128;
     __shared__ __attribute__((aligned(16))) uint8_t lds[4][TILE_BYTES];   // K even, K odd, V even, V odd
     const Geom& G = a.g;
@@ -469,8 +470,9 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
         // (tile walk, addresses, scale loads) that follows
         v8i vop[2];
         if (!FIRST) vop[0] = load_v(vprev, 0);
-        // K(i+2) replaces K(i), V(i) goes to its own buffer; the copies are issued between the
-        // MFMAs of phase 1 rather than in one burst (the load unit takes them slowly)
+        // K(i+2) replaces K(i), V(i) goes to its own buffer; the copies are issued one per step,
+        // V's between the MFMAs of phase 1 and K's in phase 2, rather than in one burst (the load
+        // unit takes them slowly)
         const bool fetch_k = it + 2 < ntiles;
         const uint8_t* ksrc = fetch_k ? k_blk(w2) : nullptr;
         const uint8_t* vsrc = v_blk(w0);
@@ -505,10 +507,10 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
                 }
             }
             if (cb < CPT) stage_chunk(2 + par, vsrc, cb);
-            else if (cb < 2 * CPT && fetch_k) stage_chunk(par, ksrc, cb - CPT);
+            else if (!K_IN_PHASE2 && cb < 2 * CPT && fetch_k) stage_chunk(par, ksrc, cb - CPT);
             __builtin_amdgcn_sched_barrier(0);
         }
-        static_assert(2 * CPT <= 8, "staging is spread over the 8 channel blocks of phase 1");
+        static_assert(2 * CPT <= 8, "at most one staging copy per step of a phase");
         if (!FIRST) pv_accumulate(7, tq[1], svv_prev);
         v8i kop[2];                      // K(i+1) has been visible since the barrier: ask for its first
         if (!LAST) kop[0] = load_k(knxt, 0);   // operand before the cross-lane reduction of the maxima
@@ -547,6 +549,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
                 pb[qb][b] = pw;
             }
             if (!LAST) qk_mfma(kop[b & 1], b);
+            if (K_IN_PHASE2 && b < CPT && fetch_k) stage_chunk(par, ksrc, b);   // K(i) was consumed last iteration
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
