@@ -583,8 +583,8 @@ def test_step_config_with_granularity_per_regime():
 
 
 # ---- full-size shapes, sampled against the oracle ---------------------------------------------
-def _sampled_parity(w, prec, window, head_picks, seed, n_interior=2):
-    run = gu.GpuRun(w)
+def _sampled_parity(w, prec, window, head_picks, seed, n_interior=2, run=None):
+    run = run or gu.GpuRun(w)
     out, vis = run.attn(prec, window=window, visited=True)
     mask = fo.tile_mask(run.g, window)
     assert np.array_equal(vis.cpu().numpy().astype(bool), mask)
@@ -630,3 +630,17 @@ def test_wan_14b_720p_fp8_sampled_in_bench_configuration():
         for h in range(0, w.heads, 7):
             ws = fo.tile_scales(fo.tile_order(run.qkv[role][h], run.g), run.g)
             assert np.array_equal(sc[h], ws)
+
+
+def test_wan_14b_720p_dense_references_and_schedule_windows_sampled():
+    """The other launches bench.py times on the 720p grid: the dense window in both precisions (the
+    reference points of the speed-up) and the two FP8 windows of the step-aware schedule."""
+    w = synth.WAN_14B_720P
+    run = gu.GpuRun(w)
+    nT, nH, nW = run.g.n_tiles_axis
+    dense = (2 * nT - 1, 2 * nH - 1, 2 * nW - 1)
+    for prec, window, pairs, head in [(fps.PREC_FP8, dense, 396900, 8), (fps.PREC_BF16, dense, 396900, 23),
+                                      (fps.PREC_FP8, (7, 5, 5), 61560, 31), (fps.PREC_FP8, (3, 3, 3), 12688, 4)]:
+        say("720p", "fp8" if prec == fps.PREC_FP8 else "bf16", window)
+        _, kept = _sampled_parity(w, prec, window, [head], seed=5, n_interior=1, run=run)
+        assert kept == pairs
