@@ -644,3 +644,34 @@ def test_wan_14b_720p_dense_references_and_schedule_windows_sampled():
         say("720p", "fp8" if prec == fps.PREC_FP8 else "bf16", window)
         _, kept = _sampled_parity(w, prec, window, [head], seed=5, n_interior=1, run=run)
         assert kept == pairs
+
+
+def test_tensors_beyond_4_gib_index_correctly():
+    """Offsets are 64-bit in every kernel: in a batch whose raster, packed and output tensors all
+    exceed 2^32 bytes, the last heads give bit for bit what the same heads give alone."""
+    import torch
+    say("tensors beyond 4 GiB")
+    w = dataclasses.replace(synth.WAN_1_3B_480P, heads=4, config_id=23)
+    small = gu.GpuRun(w)
+    reps = 200
+    big = fps.make_shape(w.heads * reps, w.grid, w.tile)
+    assert fps.packed_bytes(big, fps.PREC_FP8) > 2 ** 32
+    results = []
+    for shape, rasters in ((small.shape, small.raster),
+                           (big, [r.repeat(1, reps, 1, 1, 1, 1) for r in small.raster])):
+        assert shape is small.shape or rasters[0].numel() * 2 > 2 ** 32
+        q8 = [fps.quantize_tiles(shape, r, role, raster=True) for role, r in enumerate(rasters)]
+        o8 = fps.attn_fwd(shape, w.window, fps.PREC_FP8, q8[0][0], q8[1][0], q8[2][0],
+                          q8[0][1], q8[1][1], q8[2][1], out_dtype=torch.bfloat16, raster_out=True)
+        p16 = [fps.pack_tiles_bf16(shape, r, role, raster=True) for role, r in enumerate(rasters)]
+        o16 = fps.attn_fwd(shape, w.window, fps.PREC_BF16, p16[0][0], p16[1][0], p16[2][0],
+                           None, None, p16[2][1], out_dtype=torch.bfloat16, raster_out=True)
+        torch.cuda.synchronize()
+        n = shape.heads
+        keep = [t.view(n, -1)[-w.heads:].clone() for pair in q8 + p16 for t in pair if t is not None]
+        keep += [o.view(torch.int16).view(n, -1)[-w.heads:].clone() for o in (o8, o16)]
+        results.append(keep)
+        del q8, p16, o8, o16, rasters
+    for i, (a, b) in enumerate(zip(*results)):
+        assert torch.equal(a, b), f"tensor {i} of the last heads differs"
+    assert float(results[0][-2].view(torch.bfloat16).float().abs().max()) > 0
