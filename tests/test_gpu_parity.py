@@ -387,12 +387,18 @@ def test_fused_raster_entry_points_match_the_unfused_path(grid, tile):
             assert torch.equal(raster, fps.tile_unorder(run.shape, tiled))
 
 
-def test_two_runs_are_bit_identical(tiny):
+def test_two_runs_are_bit_identical_and_inputs_stay_untouched(tiny):
     import torch
     say("determinism")
     a = tiny.attn(fps.PREC_FP8).clone()
+    before = [t.clone() for pair in tiny.q8 for t in pair] + [t.clone() for t in tiny.raster + tiny.tiled]
     b = tiny.attn(fps.PREC_FP8)
     assert torch.equal(a, b)
+    fps.quantize_tiles(tiny.shape, tiny.raster[2], fps.ROLE_V, raster=True)
+    fps.quantize_tiles(tiny.shape, tiny.tiled[0], fps.ROLE_Q)
+    torch.cuda.synchronize()
+    after = [t for pair in tiny.q8 for t in pair] + tiny.raster + tiny.tiled
+    assert all(torch.equal(x, y) for x, y in zip(before, after))
 
 
 def _random_case(rng):
