@@ -267,6 +267,10 @@ __device__ __forceinline__ v8i make_v8i(const uint4& lo, const uint4& hi) {
 // compiler's wait-count bookkeeping does not serialise it against LDS reads of OTHER buffers; the
 // kernel waits for it explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
 // gsrc is a wave-uniform base (kept in scalar registers), lane_off the lane's byte offset from it.
+// OFF (0, 1024, 2048 or 3072) is the instruction's immediate offset: the hardware adds it to the
+// global address AND to the LDS address, so the four 1 KB pieces of a wave's 4 KB share of a tile
+// need one scalar base each side.
+template <int OFF>
 __device__ __forceinline__ void dma_chunk(const void* gsrc, uint32_t lane_off, uint32_t lds_wave_base) {
     // both are wave-uniform by construction; say so where the compiler cannot prove it
     const uint64_t p = reinterpret_cast<uint64_t>(gsrc);
@@ -276,10 +280,21 @@ __device__ __forceinline__ void dma_chunk(const void* gsrc, uint32_t lane_off, u
     lds_wave_base = __builtin_amdgcn_readfirstlane(lds_wave_base);
     asm volatile("s_mov_b32 m0, %2\n\t"
                  "s_nop 0\n\t"
-                 "global_load_lds_dwordx4 %0, %1"
+                 "global_load_lds_dwordx4 %0, %1 offset:%3"
                  :
-                 : "v"(lane_off), "s"(gsrc), "s"(lds_wave_base)
+                 : "v"(lane_off), "s"(gsrc), "s"(lds_wave_base), "n"(OFF)
                  : "memory", "m0");
+}
+// chunk c of a wave's contiguous share: base moves every four chunks, the rest rides in the offset
+__device__ __forceinline__ void dma_chunk_of(int c, const uint8_t* gsrc_wave, uint32_t lane_off, uint32_t lds_wave) {
+    const uint8_t* gs = gsrc_wave + (c >> 2) * 4096;
+    const uint32_t ld = lds_wave + (c >> 2) * 4096;
+    switch (c & 3) {
+        case 0: dma_chunk<0>(gs, lane_off, ld); break;
+        case 1: dma_chunk<1024>(gs, lane_off, ld); break;
+        case 2: dma_chunk<2048>(gs, lane_off, ld); break;
+        default: dma_chunk<3072>(gs, lane_off, ld); break;
+    }
 }
 
 // The FP8 kernel is software-pipelined inside each wave, because on this chip a wave whose next
@@ -341,9 +356,8 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 
     // chunk c (of CPT) of this thread's share of one operand tile, HBM -> lds[buf]
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the wave index, in a scalar register
-    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {
-        dma_chunk(src + c * NTHR * 16, tid * 16,
-                  lds_base + buf * TILE_BYTES + (c * NTHR + wave_s * 64) * 16);
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {   // wave w copies bytes [w, w+1) * CPT KB
+        dma_chunk_of(c, src + wave_s * (CPT * 1024), lane * 16, lds_base + buf * TILE_BYTES + wave_s * (CPT * 1024));
     };
     auto stage = [&](int buf, const uint8_t* src) FPS_INLINE {
 #pragma unroll
@@ -650,9 +664,8 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     const int ntiles = w0.n;
     auto tile_of = [&](const TileWalk& w) FPS_INLINE { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the wave index, in a scalar register
-    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {
-        dma_chunk(src + c * NTHR * 16, tid * 16,
-                  lds_base + buf * TILE_BYTES + (c * NTHR + wave_s * 64) * 16);
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {   // wave w copies bytes [w, w+1) * CPT KB
+        dma_chunk_of(c, src + wave_s * (CPT * 1024), lane * 16, lds_base + buf * TILE_BYTES + wave_s * (CPT * 1024));
     };
     auto k_blk = [&](const TileWalk& w) FPS_INLINE { return a.k + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
     auto v_blk = [&](const TileWalk& w) FPS_INLINE { return a.v + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
