@@ -23,7 +23,7 @@ FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
 BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the attention kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a
 # plain 1 GiB copy kernel (profiles/attn_fp8_wan14b-720p_counters.md); measured, not computed here.
-MEASURED_TRAFFIC_BYTES = {"wan14b-720p": 2.96e9}
+MEASURED_TRAFFIC_BYTES = {"wan14b-720p": 2.97e9}
 
 
 def kept_pairs(grid, tile, window):
