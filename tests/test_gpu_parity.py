@@ -522,6 +522,33 @@ def test_side_stream_and_graph_replay(tiny):
         assert torch.equal(out, want), rep
 
 
+def test_calls_on_two_streams_at_once_do_not_disturb_each_other(tiny):
+    """The library keeps no device state between calls: two different shapes driven from two
+    streams at the same time give what each gives alone."""
+    import torch
+    say("two streams at once")
+    other = gu.GpuRun(dataclasses.replace(synth.TINY, grid=(5, 13, 20), tile=(1, 8, 16), window=(3, 3, 3),
+                                          heads=3, n_outlier=3, config_id=29))
+    runs = [tiny, other]
+    want = []
+    for r in runs:
+        r.quantize()
+        want.append(r.attn(fps.PREC_FP8).clone())
+    outs = [torch.empty_like(o) for o in want]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]          # default priority
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    for rep in range(8):
+        for r, o, st in zip(runs, outs, streams):
+            with torch.cuda.stream(st):
+                (q, sq), (k, sk), (v, sv) = r.q8
+                fps.attn_fwd(r.shape, r.w.window, fps.PREC_FP8, q, k, v, sq, sk, sv, out=o)
+    for st in streams:
+        st.synchronize()
+    for o, x in zip(outs, want):
+        assert torch.equal(o, x)
+
+
 def test_step_config_selects_regime(tiny):
     import torch
     say("step config")
