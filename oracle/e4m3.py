@@ -82,23 +82,3 @@ def round_to_e4m3(y: np.ndarray) -> np.ndarray:
 def encode(y: np.ndarray) -> np.ndarray:
     """Byte codes of round_to_e4m3(y)."""
     return encode_scaled(y, 1.0)
-
-
-def rounding_slack(y: np.ndarray, tau: float) -> np.ndarray:
-    """Comparator helper, not part of the method: for y >= 0, by how much (in units of y) the
-    rounded value could legitimately differ when y is known only to relative accuracy tau.
-
-    Normal range (y >= 2^-6): one grid spacing if y lies within relative tau of a rounding
-    midpoint, else 0.  Subnormal range (y < 2^-6, spacing 2^-9): half a spacing always, because
-    an online evaluation that rounds such an element against an earlier, smaller row reference
-    resolves it on a finer grid than the final one; plus one spacing near a midpoint."""
-    y = np.asarray(y, dtype=np.float64)
-    a = np.minimum(y, FP8_MAX)
-    _, e = np.frexp(a)
-    q = np.maximum(e - 4, _SUBNORMAL_QUANTUM)
-    quantum = np.ldexp(1.0, q)
-    t = a / quantum
-    dist = np.abs(t - np.floor(t) - 0.5) * quantum        # distance to the cell's midpoint
-    near = dist <= tau * np.maximum(a, 2.0 ** -10)
-    sub = a < 2.0 ** _MIN_NORMAL_EXP
-    return np.where(near, quantum, 0.0) + np.where(sub, 0.5 * quantum, 0.0)

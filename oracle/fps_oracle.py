@@ -285,8 +285,9 @@ def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vsc
     Returns O float64 [len(q_tiles)*TS, d] for the requested query tiles (default all), rows of
     padded query slots being 0.  With return_parts=True also returns, per requested query tile, the
     intermediate quantities (key columns, dequantised scores S', row reference m, un-normalised P,
-    denominator l, quantised P, dequantised V rows, raw code dot products and the per-pair score
-    scale) so that a comparator can inspect individual rounding decisions.
+    denominator l, quantised P, dequantised V rows, raw code dot products, the sums of their
+    absolute products and the per-pair score scale) so that a comparator can inspect individual
+    rounding decisions.
     """
     M, TS = g.M, g.TS
     d = q_tiled.shape[-1]
@@ -340,8 +341,10 @@ def attention(q_tiled, k_tiled, v_tiled, g: Geometry, window, prec=PREC_FP8, vsc
         o[~rows_valid] = 0.0
         out[n * TS:(n + 1) * TS] = o
         if return_parts:
-            parts.append(dict(u=u, key_tiles=vs, cols=cols, raw=raw, pair_scale=pair_scale, S=S, m=m,
-                              p=p, l=l, ph=ph, v=vh[cols], rows_valid=rows_valid))
+            # sum_c |q_c k_c|: the yardstick against which a hardware accumulation error is measured
+            absraw = np.abs(Qu) @ np.abs(Kw).T
+            parts.append(dict(u=u, key_tiles=vs, cols=cols, raw=raw, absraw=absraw, pair_scale=pair_scale,
+                              S=S, m=m, p=p, l=l, ph=ph, v=vh[cols], rows_valid=rows_valid))
     if return_parts:
         return out, parts
     return out
