@@ -6,8 +6,13 @@ already resident in HBM in raster order: tile ordering + per-tile FP8 quantisati
 fused kernel per tensor) and the sliding-tile attention kernel, whose epilogue writes the output
 back in raster order.  Prints ONE JSON line.
 
+After the timed steps the same process also times, each outside the headline figure: the dense BF16
+and dense FP8 launches on the same grid (the speed-up's reference points), the 50-call
+denoising-step-aware schedule (Eq. 6) on fresh inputs per call, and the CPU oracle on a bounded
+sample.
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-dense] [--no-cpu]
-                  [--schedule] [--variants]
+                  [--no-schedule] [--variants] [--window-ablation]
 """
 import argparse
 import json
@@ -21,9 +26,13 @@ if ROOT not in sys.path:
 
 FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
 BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the attention kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a
-# plain 1 GiB copy kernel (profiles/attn_fp8_wan14b-720p_counters.md); measured, not computed here.
-MEASURED_TRAFFIC_BYTES = {"wan14b-720p": 2.97e9}
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
+# HBM bytes per launch of the attention kernel: rocprofv3 FETCH_SIZE and WRITE_SIZE, each scaled by
+# what the same counter reads for a plain 1 GiB copy kernel.  Taken from the committed profile, NOT
+# measured by this run (a counter run cannot share a process with the timing); the launches of one
+# profile run spread as stated there.
+PROFILED_TRAFFIC = {"wan14b-720p": {"bytes": 2.97e9, "range": [2.96e9, 3.84e9],
+                                    "source": "profiles/attn_fp8_wan14b-720p_counters.md"}}
 
 
 def kept_pairs(grid, tile, window):
@@ -46,8 +55,9 @@ def main():
     ap.add_argument("--cpu-heads", type=int, default=4, help="heads in the timed CPU oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for the profiler's traffic counters)")
-    ap.add_argument("--schedule", action="store_true",
-                    help="also run the 50-call denoising-step-aware schedule (Eq. 6) on fresh inputs per call")
+    ap.add_argument("--no-schedule", action="store_true",
+                    help="skip the 50-call denoising-step-aware schedule (Eq. 6), e.g. under a profiler")
+    ap.add_argument("--schedule", action="store_true", help="(the schedule runs by default; kept for old command lines)")
     ap.add_argument("--variants", action="store_true",
                     help="also time the variants of the path on the same grid: per-channel V scales, BF16 with "
                          "the sparse window, the shifted-window edge rule, other tile shapes")
@@ -137,6 +147,12 @@ def main():
     mfma_sustained = mfma_flop / (m0.elapsed_time(m1) * 1e-3) / 1e12
     del sink
 
+    # bytes the three quantise launches really move: the un-padded bf16 raster read, the packed codes
+    # (padded to whole tiles) and the scales written
+    tokens = w.grid[0] * w.grid[1] * w.grid[2]
+    quant_bytes = 3.0 * w.heads * (2.0 * tokens * 128 + 1.0 * L * 128 + 4.0 * M)
+    traffic = PROFILED_TRAFFIC.get(w.name, {})
+
     result = {
         "metric": "effective TFLOP/s + ms/call, FP8 3D sliding-tile attention, Wan-14B 720p shape",
         "value": flop / (ms_per_step * 1e-3) / 1e12,
@@ -153,12 +169,18 @@ def main():
         "attention_tflops_real_tokens_only": useful_flop / (attn_ms * 1e-3) / 1e12,
         "mfma_only_sustained_tflops": mfma_sustained,
         "attention_frac_of_sustained_mfma": flop / (attn_ms * 1e-3) / 1e12 / mfma_sustained,
-        "quantize_GBps": 3.0 * 3 * w.heads * L * 128 / (quant_ms * 1e-3) / 1e9,
+        "quantize_GBps": quant_bytes / (quant_ms * 1e-3) / 1e9,
         "roofline": {"bound": "mfma", "kernel": "attn_fp8_kernel", "achieved": flop / (attn_ms * 1e-3) / 1e12,
                      "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop / (attn_ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-                     "algorithmic_bytes": 3.0 * w.heads * L * 128 + 2.0 * w.heads * w.grid[0] * w.grid[1] * w.grid[2] * 128},
+                     "traffic": traffic.get("bytes"), "traffic_range": traffic.get("range"),
+                     "traffic_source": traffic.get("source", "not profiled for this workload"),
+                     "algorithmic_bytes": 3.0 * w.heads * L * 128 + 2.0 * w.heads * tokens * 128},
+        # second entry: the quantise pass is the HBM-bound kernel of the path (three launches per step)
+        "roofline_quantize": {"bound": "hbm", "kernel": "quantize_tiles_kernel (x3: Q, K, V)",
+                              "achieved": quant_bytes / (quant_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+                              "unit": "GB/s", "frac": quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                              "traffic": None, "algorithmic_bytes": quant_bytes},
         "paper_context": {"kernel_speedup_vs_bf16_H20": 7.09, "e2e_speedup_vs_bf16_H20": 4.96},
     }
 
@@ -198,8 +220,9 @@ def main():
     if args.window_ablation:
         result["window_ablation"] = run_window_ablation(dev)
 
-    if args.schedule:
-        del raster
+    if not args.no_schedule:
+        del raster, packed, scales, out_raster
+        torch.cuda.empty_cache()
         result["schedule"] = run_schedule(w, shape, dev)
 
     if not args.no_cpu:

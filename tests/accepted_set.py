@@ -24,9 +24,12 @@ import numpy as np
 
 from oracle import e4m3
 
-# Accumulation accuracy of the E4M3 matrix instruction relative to sum_c |q_c k_c|: measured up to
-# 2^-12.6 on uniformly random codes and about 2^-14 on Gaussian data with outlier channels.
-ACC_EPS = 2.0 ** -12
+# Accumulation accuracy of the E4M3 matrix instruction relative to sum_c |q_c k_c|.  Measured on the
+# box: the error is symmetric around zero, about 2^-16.5 of that sum on average, and its largest
+# values follow the largest single product of the row (up to 5.5 * 2^-13 of it: an outlier-channel
+# product beside 127 small ones), which on Gaussian data with x8 outlier channels reaches
+# 1.5 * 2^-12 of the sum.  The GPU tests assert the bound below on every tile they compare.
+ACC_EPS = 2.0 ** -11
 # The kernel evaluates 448 * 2^(S' - m) in float32: the product of three scales, one fma and the
 # hardware exponential.  Exponent error <= |S'| * EXP_ABS (scale product and fma roundings), and a
 # relative error EXP_REL on the result (v_exp_f32 is accurate to about one ulp).
@@ -41,10 +44,11 @@ def score_halfwidth(part, acc_eps=ACC_EPS):
     return acc_eps * part["absraw"] * part["pair_scale"]
 
 
-def fp8_slack(part, ref_rows, acc_eps=ACC_EPS, exp_abs=EXP_ABS, exp_rel=EXP_REL):
+def fp8_slack(part, ref_rows, acc_eps=ACC_EPS, exp_abs=EXP_ABS, exp_rel=EXP_REL, pv_eps=None):
     """Per output element of one query tile: the largest distance from the oracle's output
     `ref_rows` that a result can have when every score is only known to lie within the hardware's
-    accumulation bound of the oracle's exact score.  Returns (slack [TS, d], stats dict).
+    accumulation bound of the oracle's exact score.  Returns (slack [TS, d], stats dict,
+    may_differ [TS, keys]: the P elements for which more than one value is acceptable).
 
     Terms.  (a) P codes: y = 448 p lies in [y_lo, y_hi]; rounding is monotone, so the codes a
     correct implementation may produce are those between round(y_lo) and round(y_hi).  (b) An
@@ -57,6 +61,7 @@ def fp8_slack(part, ref_rows, acc_eps=ACC_EPS, exp_abs=EXP_ABS, exp_rel=EXP_REL)
     carries the same relative accumulation bound.
     """
     fmax = e4m3.FP8_MAX
+    pv_eps = acc_eps if pv_eps is None else pv_eps
     delta = score_halfwidth(part, acc_eps) + np.abs(part["S"]) * exp_abs
     grow = np.exp2(delta) * (1.0 + exp_rel)
     y = fmax * part["p"]
@@ -76,6 +81,7 @@ def fp8_slack(part, ref_rows, acc_eps=ACC_EPS, exp_abs=EXP_ABS, exp_rel=EXP_REL)
     up_rows = (part["S"] + delta).max(axis=1) > part["m"]
     sub_up = up_rows[:, None] & (y_lo < 2 * MIN_NORMAL)
     d = np.where(sub_up, np.maximum(d, reach + SUB_SPACING), d)
+    may_differ = d > 0
     d /= fmax
     # (d) denominator
     l = part["l"]
@@ -84,11 +90,11 @@ def fp8_slack(part, ref_rows, acc_eps=ACC_EPS, exp_abs=EXP_ABS, exp_rel=EXP_REL)
     absv = np.abs(part["v"])
     slack = (d @ absv) / l_lo[:, None]
     slack += np.abs(ref_rows) * (np.maximum(l_hi - l, l - l_lo) / l_lo)[:, None]
-    slack += acc_eps * ((part["ph"] + d) @ absv) / l_lo[:, None]        # (e)
+    slack += pv_eps * ((part["ph"] + d) @ absv) / l_lo[:, None]         # (e)
     slack[~part["rows_valid"]] = 0.0
     stats = dict(p_elems=int(y.size), ambiguous=int(np.count_nonzero(ambiguous)),
                  rows_ref_may_rise=int(np.count_nonzero(up_rows & part["rows_valid"])))
-    return slack, stats
+    return slack, stats, may_differ
 
 
 def scores_within_model(raw_hw, part, acc_eps=ACC_EPS):

@@ -96,7 +96,7 @@ def test_exact_scores_in_any_tile_order_need_almost_no_slack():
 def test_without_uncertainty_only_the_subnormal_range_has_slack():
     g, ref, parts = case(8)
     p = parts[5]
-    slack, st = acs.fp8_slack(p, ref[5 * g.TS:6 * g.TS], acc_eps=0.0, exp_abs=0.0, exp_rel=0.0)
+    slack, st, _ = acs.fp8_slack(p, ref[5 * g.TS:6 * g.TS], acc_eps=0.0, exp_abs=0.0, exp_rel=0.0)
     assert st["ambiguous"] == 0 and st["rows_ref_may_rise"] == 0
     y = e4m3.FP8_MAX * p["p"]
     bound = ((np.where(y < acs.MIN_NORMAL, acs.SUB_SPACING * 0.75, 0.0) / e4m3.FP8_MAX) @ np.abs(p["v"])) \
@@ -107,8 +107,8 @@ def test_without_uncertainty_only_the_subnormal_range_has_slack():
     one = dict(p, p=np.array([[pv]]), ph=np.array([[18.0 / 448]]),
                S=np.array([[0.0]]), m=np.array([1.0]), l=np.array([pv]), v=np.array([[1.0]]),
                absraw=np.array([[1.0]]), pair_scale=np.array([[1.0]]), rows_valid=np.array([True]))
-    s_wide, st_wide = acs.fp8_slack(one, np.zeros((1, 1)), acc_eps=2.0 ** -14, exp_abs=0.0, exp_rel=0.0)
-    s_none, st_none = acs.fp8_slack(one, np.zeros((1, 1)), acc_eps=2.0 ** -20, exp_abs=0.0, exp_rel=0.0)
+    s_wide, st_wide, _ = acs.fp8_slack(one, np.zeros((1, 1)), acc_eps=2.0 ** -14, exp_abs=0.0, exp_rel=0.0)
+    s_none, st_none, _ = acs.fp8_slack(one, np.zeros((1, 1)), acc_eps=2.0 ** -20, exp_abs=0.0, exp_rel=0.0)
     assert st_wide["ambiguous"] == 1 and s_wide[0, 0] >= (2.0 / 448) / pv      # 16 is acceptable too
     assert st_none["ambiguous"] == 0 and s_none[0, 0] <= 2 * 2.0 ** -20            # PV accumulation only
 
