@@ -63,6 +63,7 @@ constexpr size_t kTablesOffset = (sizeof(AttnArgs) + 7) & ~size_t(7);   // kerna
 constexpr float kLog2eOverSqrtD = 0.12751743f;   // log2(e) / sqrt(128)
 constexpr float kLog2Of448 = 8.8073549f;          // log2(448)
 constexpr float kFp16PScaleLog2 = 14.0f;          // BF16 mode holds 2^14 * P in fp16
+constexpr float kMaxDrift = 64.0f;                // largest m - m_base before O and l are moved to a new reference
 constexpr int kStoreRegionBytes = 16 * (512 + 16);  // per-wave LDS region of the output transpose
 
 // Scales are read-only for the whole launch and indexed uniformly: reading them through the constant
@@ -335,7 +336,15 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     v8i qop[2];
     float m_run[2] = {-INFINITY, -INFINITY};
     float l_run[2] = {0.f, 0.f};                           // running sum of 448 * P
-    float alpha_prev[2] = {1.f, 1.f};                      // rescale owed to O before the delayed PV
+    float alpha_prev[2] = {1.f, 1.f};                      // VCH: rescale owed to O before the delayed PV
+    // Per-tile V scales: O and l are kept relative to a FIXED reference m_base (that of the first
+    // tile) and each tile's contribution is weighted by 2^(m - m_base) >= 1 instead -- the weight
+    // rides in the multiplier of the fma that applies s^V anyway, so a moving row reference costs
+    // nothing (rescaling O costs 64 multiplications per wave whenever ANY of its 32 rows moves,
+    // which is two tiles in three).  Powers of two commute with fp32 rounding: same results.
+    float m_base[2] = {0.f, 0.f};
+    float w_cur[2] = {1.f, 1.f};                           // 2^(m - m_base) of the tile whose softmax is taken
+    float w_prev[2] = {0.f, 0.f};                          // s^V * 2^(m - m_base) of the tile whose PV is owed
     v4f acc[2][8];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -408,11 +417,11 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     };
     // O^T(cb) += s^V * t, pinned where it is written so that t does not stay live (the compiler
     // otherwise sinks all sixteen updates below the loop and spills)
-    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) FPS_INLINE {
+    auto pv_accumulate = [&](int cb, const v4f (&t)[2], const float (&w)[2]) FPS_INLINE {
         if (VCH) return;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            acc[qb][cb] += t[qb] * svv;
+            acc[qb][cb] += t[qb] * w[qb];
             asm volatile("" : "+v"(acc[qb][cb]));
         }
     };
@@ -444,7 +453,8 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
             }
         }
     };
-    auto rescale_acc = [&]() FPS_INLINE {                             // the row reference rarely moves
+    auto rescale_acc = [&]() FPS_INLINE {                             // VCH only
+        if (!VCH) return;
         if (__any(alpha_prev[0] != 1.0f || alpha_prev[1] != 1.0f)) {
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb)
@@ -463,7 +473,6 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     for (int b = 0; b < NB; ++b) qk_mfma(load_k(lds[0], b), b);
     mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
 
-    float svv_prev = 0.f;
     float sc_next = sqc * load_uniform(a.sk, (tile0 + tile_of(w0)) * NS + w0.js);   // scales of the coming block
     float sv_next = VCH ? 1.f : load_uniform(a.sv, (tile0 + tile_of(w0)) * NS + w0.js);
     // One iteration.  FIRST: there is no previous tile whose PV is owed.  LAST: there is no next
@@ -511,7 +520,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
             if (!FIRST) {
                 if (cb + 1 < 8) vop[(cb + 1) & 1] = load_v(vprev, cb + 1);
                 pv_mfma(vop[cb & 1], tq[cb & 1], cb);
-                if (cb > 0) pv_accumulate(cb - 1, tq[(cb - 1) & 1], svv_prev);
+                if (cb > 0) pv_accumulate(cb - 1, tq[(cb - 1) & 1], w_prev);
             }
             if (cb >= 1 && cb < NB) {
 #pragma unroll
@@ -525,7 +534,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
             __builtin_amdgcn_sched_barrier(0);
         }
         static_assert(2 * CPT <= 8, "at most one staging copy per step of a phase");
-        if (!FIRST) pv_accumulate(7, tq[1], svv_prev);
+        if (!FIRST) pv_accumulate(7, tq[1], w_prev);
         v8i kop[2];                      // K(i+1) has been visible since the barrier: ask for its first
         if (!LAST) kop[0] = load_k(knxt, 0);   // operand before the cross-lane reduction of the maxima
         float cm[2];
@@ -534,10 +543,29 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
             float t = mx[qb];
             t = max_over_row_lanes(t);
             const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(t * sc));
-            alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
+            if (VCH) {
+                alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
+            } else {
+                if (FIRST) m_base[qb] = m_new;
+                w_cur[qb] = fast_exp2(m_new - m_base[qb]);
+            }
             m_run[qb] = m_new;
             // 448 * 2^(S' - m) = 2^(S' + (log2(448) - m)): the factor 448 rides in the exponent
             cm[qb] = kLog2Of448 - m_new;
+        }
+        // O (complete up to tile i-1 here) and l move to a new reference only when a row has drifted
+        // kMaxDrift above its own: 448 * sum|v| * 2^kMaxDrift stays far inside the fp32 range
+        if (!VCH && !FIRST &&
+            __any(m_run[0] - m_base[0] > kMaxDrift || m_run[1] - m_base[1] > kMaxDrift)) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const float down = fast_exp2(m_base[qb] - m_run[qb]);
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= down;
+                l_run[qb] *= down;
+                m_base[qb] = m_run[qb];
+                w_cur[qb] = 1.0f;
+            }
         }
 
         // ---- phase 2: P(i) and its FP8 codes  |  early QK(i+1) ------------------------------
@@ -567,9 +595,12 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
+        for (int qb = 0; qb < 2; ++qb) {
+            if (VCH) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
+            else     l_run[qb] = __builtin_fmaf(rs[qb], w_cur[qb], l_run[qb]);
+            w_prev[qb] = svv * w_cur[qb];
+        }
         if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
-        svv_prev = svv;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the staged tiles landed
     };
     using T_ = std::true_type;
@@ -590,7 +621,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) {
             pv_mfma(load_v(vlast, cb), tq, cb);
-            pv_accumulate(cb, tq, svv_prev);
+            pv_accumulate(cb, tq, w_prev);
         }
     }
 
@@ -644,7 +675,11 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     Bf16x8 qop[2][4];
     float m_run[2] = {-INFINITY, -INFINITY};
     float l_run[2] = {0.f, 0.f};
-    float alpha_prev[2] = {1.f, 1.f};
+    // O and l relative to the fixed reference m_base, contributions weighted by 2^(m - m_base): see
+    // the FP8 kernel
+    float m_base[2] = {0.f, 0.f};
+    float w_cur[2] = {1.f, 1.f};
+    float w_prev[2] = {0.f, 0.f};
     v4f acc[2][8];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -701,10 +736,10 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
             t[qb] = r;
         }
     };
-    auto pv_accumulate = [&](int cb, const v4f (&t)[2], float svv) FPS_INLINE {
+    auto pv_accumulate = [&](int cb, const v4f (&t)[2], const float (&w)[2]) FPS_INLINE {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            acc[qb][cb] += t[qb] * svv;
+            acc[qb][cb] += t[qb] * w[qb];
             asm volatile("" : "+v"(acc[qb][cb]));
         }
     };
@@ -736,15 +771,6 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
             }
         }
     };
-    auto rescale_acc = [&]() FPS_INLINE {
-        if (__any(alpha_prev[0] != 1.0f || alpha_prev[1] != 1.0f)) {
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= alpha_prev[qb];
-        }
-    };
-
     // prologue: K(0) staged, S(0) computed
 #pragma unroll
     for (int c = 0; c < CPT; ++c) stage_chunk(0, k_blk(w0), c);
@@ -754,7 +780,6 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     for (int b = 0; b < NB; ++b) qk_block(b);
     mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
 
-    float svv_prev = 0.f;
     auto iteration = [&](auto first_tag, auto last_tag) FPS_INLINE {
         constexpr bool FIRST = decltype(first_tag)::value;
         constexpr bool LAST = decltype(last_tag)::value;
@@ -766,7 +791,6 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
         __syncthreads();                 // every wave has finished QK(i): the K buffer is free; V(i-1) visible
 
         // ---- phase 1: row maxima of S(i)  |  delayed PV(i-1)  |  K(i+1) streams in ------------
-        if (!FIRST) rescale_acc();
         float mx[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
@@ -777,7 +801,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
             if (!FIRST) {
                 v4f tq[2];
                 pv_block(cb, tq);
-                pv_accumulate(cb, tq, svv_prev);
+                pv_accumulate(cb, tq, w_prev);
             }
             if (cb >= 1 && cb < NB) {
 #pragma unroll
@@ -796,12 +820,24 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
             float t = mx[qb];
             t = max_over_row_lanes(t);
             const float m_new = __builtin_fmaxf(m_run[qb], __builtin_ceilf(t * sc));
-            alpha_prev[qb] = fast_exp2(m_run[qb] - m_new);
+            if (FIRST) m_base[qb] = m_new;
+            w_cur[qb] = fast_exp2(m_new - m_base[qb]);
             m_run[qb] = m_new;
             // 2^14 * 2^(S' - m): the factor rides in the exponent and cancels against the row sum,
             // which is taken of the same scaled values; it keeps weights down to 2^-28 in fp16's
             // normal range (a dense row over thousands of keys has many weights below 2^-14)
             cm[qb] = kFp16PScaleLog2 - m_new;
+        }
+        if (!FIRST && __any(m_run[0] - m_base[0] > kMaxDrift || m_run[1] - m_base[1] > kMaxDrift)) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {               // O is complete up to tile i-1 here
+                const float down = fast_exp2(m_base[qb] - m_run[qb]);
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) acc[qb][cb] *= down;
+                l_run[qb] *= down;
+                m_base[qb] = m_run[qb];
+                w_cur[qb] = 1.0f;
+            }
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // K(i+1): this thread's share landed
         __syncthreads();                 // every wave has finished PV(i-1): the V buffer is free; K(i+1) visible
@@ -834,11 +870,13 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) l_run[qb] = l_run[qb] * alpha_prev[qb] + rs[qb];
+        for (int qb = 0; qb < 2; ++qb) {
+            l_run[qb] = __builtin_fmaf(rs[qb], w_cur[qb], l_run[qb]);
+            w_prev[qb] = svv * w_cur[qb];
+        }
         w0.next();
         w1.next();
         if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
-        svv_prev = svv;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // V(i): this thread's share landed
     };
     using T_ = std::true_type;
@@ -852,13 +890,12 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     }
     // epilogue: the last tile's PV
     __syncthreads();
-    rescale_acc();
     {
         v4f tq[2];
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) {
             pv_block(cb, tq);
-            pv_accumulate(cb, tq, svv_prev);
+            pv_accumulate(cb, tq, w_prev);
         }
     }
 
