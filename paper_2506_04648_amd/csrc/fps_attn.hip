@@ -308,7 +308,14 @@ __device__ __forceinline__ void dma_chunk_of(int c, const uint8_t* gsrc_wave, ui
 // K(i+2) and V(i) stream into LDS during iteration i; one barrier per iteration.
 // VCH: V carries one scale per channel (the paper's variant) instead of one per tile; the PV MFMA
 // then accumulates straight into O and the scales are applied once in the epilogue.
-template <int BS, bool VCH, bool MB>
+// NK: what the host knows of the number of key blocks a work item walks -- kOneKeyBlock (every
+// item exactly one), kManyKeyBlocks (every item at least two), kAnyKeyBlocks.  With one-block
+// tiles it is one or the other for the whole launch; compiling the two cases apart keeps the
+// single-block path from joining the pipelined one (the join costs a dozen registers that the
+// compiler then spills to scratch memory across the whole main loop: 0.2 GB of HBM writes per call
+// at the 720p shape).
+enum { kAnyKeyBlocks = 0, kOneKeyBlock = 1, kManyKeyBlocks = 2 };
+template <int BS, bool VCH, bool MB, int NK>
 __global__ __launch_bounds__(BS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_fp8_kernel(AttnArgs a, MaskTables) {
     constexpr int NB = BS / 16;
@@ -605,7 +612,13 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
     };
     using T_ = std::true_type;
     using F_ = std::false_type;
-    if (ntiles == 1) {
+    if constexpr (NK == kOneKeyBlock) {
+        iteration(T_{}, T_{}, 0);
+    } else if constexpr (NK == kManyKeyBlocks) {
+        iteration(T_{}, F_{}, 0);
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{}, it);
+        iteration(F_{}, T_{}, ntiles - 1);
+    } else if (ntiles == 1) {
         iteration(T_{}, T_{}, 0);
     } else {
         iteration(T_{}, F_{}, 0);
@@ -647,7 +660,7 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 // ---------------------------------------------------------------------------------------------
 union Bf16x8 { uint4 u; v8bf v; v8h h; };
 
-template <int BS, bool MB>
+template <int BS, bool MB, int NK>
 __global__ __launch_bounds__(BS * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_bf16_kernel(AttnArgs a, MaskTables) {
     constexpr int NB = BS / 16;
@@ -881,7 +894,13 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
     };
     using T_ = std::true_type;
     using F_ = std::false_type;
-    if (ntiles == 1) {
+    if constexpr (NK == kOneKeyBlock) {
+        iteration(T_{}, T_{});
+    } else if constexpr (NK == kManyKeyBlocks) {
+        iteration(T_{}, F_{});
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{});
+        iteration(F_{}, T_{});
+    } else if (ntiles == 1) {
         iteration(T_{}, T_{});
     } else {
         iteration(T_{}, F_{});
@@ -1026,20 +1045,35 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     const int grid = a.chunk * 8;
     const bool multi = g.KB > 1;
     const bool vch = vscale == FPS_VSCALE_CHANNEL;
+    // one-block tiles: every work item walks as many key blocks as its window has tiles, and a corner
+    // tile of the grid has the fewest -- one exactly when no axis has both a radius and a neighbour
+    const int corner = (a.rt < g.nT ? a.rt + 1 : g.nT) * (a.rh < g.nH ? a.rh + 1 : g.nH) *
+                       (a.rw < g.nW ? a.rw + 1 : g.nW);
+    const bool one = corner == 1;
+    // tiles of several blocks: a lower bound on the key blocks of any item
+    const bool many = (long long)corner * (g.KB < g.kb_last ? g.KB : g.kb_last) >= 2;
 #define FPS_LAUNCH_FP8(BS_, THREADS_)                                                              \
     do {                                                                                           \
-        if (multi) {                                                                               \
-            if (vch) attn_fp8_kernel<BS_, true, true><<<grid, THREADS_, 0, st>>>(a, t);            \
-            else     attn_fp8_kernel<BS_, false, true><<<grid, THREADS_, 0, st>>>(a, t);           \
+        if (multi && many) {                                                                       \
+            if (vch) attn_fp8_kernel<BS_, true, true, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);       \
+            else     attn_fp8_kernel<BS_, false, true, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);      \
+        } else if (multi) {                                                                        \
+            if (vch) attn_fp8_kernel<BS_, true, true, kAnyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);        \
+            else     attn_fp8_kernel<BS_, false, true, kAnyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);       \
+        } else if (one) {                                                                          \
+            if (vch) attn_fp8_kernel<BS_, true, false, kOneKeyBlock><<<grid, THREADS_, 0, st>>>(a, t);        \
+            else     attn_fp8_kernel<BS_, false, false, kOneKeyBlock><<<grid, THREADS_, 0, st>>>(a, t);       \
         } else {                                                                                   \
-            if (vch) attn_fp8_kernel<BS_, true, false><<<grid, THREADS_, 0, st>>>(a, t);           \
-            else     attn_fp8_kernel<BS_, false, false><<<grid, THREADS_, 0, st>>>(a, t);          \
+            if (vch) attn_fp8_kernel<BS_, true, false, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);      \
+            else     attn_fp8_kernel<BS_, false, false, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);     \
         }                                                                                          \
     } while (0)
 #define FPS_LAUNCH_BF16(BS_, THREADS_)                                                             \
     do {                                                                                           \
-        if (multi) attn_bf16_kernel<BS_, true><<<grid, THREADS_, 0, st>>>(a, t);                   \
-        else       attn_bf16_kernel<BS_, false><<<grid, THREADS_, 0, st>>>(a, t);                  \
+        if (multi && many) attn_bf16_kernel<BS_, true, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
+        else if (multi) attn_bf16_kernel<BS_, true, kAnyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
+        else if (one) attn_bf16_kernel<BS_, false, kOneKeyBlock><<<grid, THREADS_, 0, st>>>(a, t);  \
+        else          attn_bf16_kernel<BS_, false, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
     } while (0)
     if (prec == FPS_PREC_FP8) {
         if (g.BS == 128) FPS_LAUNCH_FP8(128, 256); else FPS_LAUNCH_FP8(32, 64);
