@@ -722,6 +722,7 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
 
     v4f s[2][NB];
     Bf16x8 pop[2][NKK];                                    // P^T in fp16, 8 keys per operand
+    Bf16x8 ring[4];                                        // MFMA operands on their way from LDS
 
     auto qk_block = [&](int b) FPS_INLINE {                           // S(b) = K(b) Q^T, both query blocks
         Bf16x8 kop[4];
@@ -804,29 +805,57 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
         __syncthreads();                 // every wave has finished QK(i): the K buffer is free; V(i-1) visible
 
         // ---- phase 1: row maxima of S(i)  |  delayed PV(i-1)  |  K(i+1) streams in ------------
+        // One step per MFMA pair (the two query blocks against one V operand).  The operands come
+        // through a ring of four registers, requested three pairs ahead; the vector work of the
+        // step -- a quarter of the previous channel block's accumulation and of this block's row
+        // maxima -- sits between the two MFMAs.  K's copies are all issued in the first half, so
+        // that they have landed when the phase ends.
         float mx[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
             mx[qb] = __builtin_fmaxf(__builtin_fmaxf(s[qb][0][0], s[qb][0][1]),
                                      __builtin_fmaxf(s[qb][0][2], s[qb][0][3]));
+        constexpr int NPV = 8 * NKK;                       // pairs of phase 1
+        auto v_operand = [&](int j) FPS_INLINE { return ldsV4[((j % NKK) * 8 + j / NKK) * 64 + lane]; };
+        v4f tq[2][2];                                      // a block's raw product waits one block for its fma
+        // quarter `part` of the vector work that accompanies channel block cb: a row-maximum step,
+        // and in quarters 1 and 2 the accumulation of block cb - 1 for one query block (its last
+        // MFMA was issued at least two MFMAs earlier, so the fma does not wait for it)
+        auto phase1_valu = [&](int cb, int part) FPS_INLINE {
+            const int qb = part >> 1, h = part & 1;
+            if (cb >= 1 && cb < NB)
+                mx[qb] = __builtin_fmaxf(__builtin_fmaxf(mx[qb], s[qb][cb][2 * h]), s[qb][cb][2 * h + 1]);
+            if (!FIRST && cb >= 1 && (part == 1 || part == 2)) {
+                acc[part - 1][cb - 1] += tq[(cb - 1) & 1][part - 1] * w_prev[part - 1];
+                asm volatile("" : "+v"(acc[part - 1][cb - 1]));
+            }
+        };
+        if (!FIRST) {
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
+            for (int j = 0; j < 3 && j < NPV; ++j) ring[j].u = v_operand(j);
+        }
+#pragma unroll
+        for (int j = 0; j < NPV; ++j) {
+            const int cb = j / NKK, kk = j % NKK;
             if (!FIRST) {
-                v4f tq[2];
-                pv_block(cb, tq);
-                pv_accumulate(cb, tq, w_prev);
+                if (j + 3 < NPV) ring[(j + 3) & 3].u = v_operand(j + 3);
+                tq[cb & 1][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                    ring[j & 3].h, pop[0][kk].h, kk == 0 ? v4f{0.f, 0.f, 0.f, 0.f} : tq[cb & 1][0], 0, 0, 0);
             }
-            if (cb >= 1 && cb < NB) {
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    mx[qb] = __builtin_fmaxf(__builtin_fmaxf(mx[qb], s[qb][cb][0]), s[qb][cb][1]);
-                    mx[qb] = __builtin_fmaxf(__builtin_fmaxf(mx[qb], s[qb][cb][2]), s[qb][cb][3]);
-                }
+            for (int part = kk * (4 / NKK); part < (kk + 1) * (4 / NKK); ++part) phase1_valu(cb, part);
+            if (!FIRST)
+                tq[cb & 1][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                    ring[j & 3].h, pop[1][kk].h, kk == 0 ? v4f{0.f, 0.f, 0.f, 0.f} : tq[cb & 1][1], 0, 0, 0);
+            if (kk == NKK - 1) asm volatile("" : "+v"(mx[0]), "+v"(mx[1]));
+            if (!LAST && kk == 0 && cb < 4) {
+                stage_chunk(0, ksrc, 2 * cb);
+                stage_chunk(0, ksrc, 2 * cb + 1);
             }
-            if (!LAST && cb < CPT) stage_chunk(0, ksrc, cb);
             __builtin_amdgcn_sched_barrier(0);
         }
-        static_assert(CPT <= 8, "K staging is spread over the 8 channel blocks of phase 1");
+        if (!FIRST) pv_accumulate(7, tq[1], w_prev);
+        static_assert(CPT == 8, "K staging: two chunks in each of the first four channel blocks");
         float cm[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -856,31 +885,52 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
         __syncthreads();                 // every wave has finished PV(i-1): the V buffer is free; K(i+1) visible
 
         // ---- phase 2: P(i) in fp16  |  early QK(i+1)  |  V(i) streams in -----------------------
+        // Same stepping.  The exponentials of key block b free that block's score registers, so
+        // the MFMA pairs that refill them run one block behind: step (b, ks) carries a quarter of
+        // block b's vector work between the two MFMAs of pair ks of block b - 1; the pairs of the
+        // last block follow on their own.
         float rs[2] = {0.f, 0.f};
-        constexpr int DMA_PER_BLOCK = (CPT + NB - 1) / NB;
+        constexpr int NQK = NB * 4;
+        auto k_operand = [&](int j) FPS_INLINE { return ldsK4[j * 64 + lane]; };
+        auto qk_pair_half = [&](int j, int qb) FPS_INLINE {
+            const int b = j >> 2, ks = j & 3;
+            s[qb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                ring[j & 3].v, qop[qb][ks].v, ks == 0 ? v4f{0.f, 0.f, 0.f, 0.f} : s[qb][b], 0, 0, 0);
+        };
+        auto phase2_valu = [&](int b, int part) FPS_INLINE {
+            const int qb = part >> 1, h = part & 1;
+            const float p0 = fast_exp2(__builtin_fmaf(s[qb][b][2 * h], sc, cm[qb]));
+            const float p1 = fast_exp2(__builtin_fmaf(s[qb][b][2 * h + 1], sc, cm[qb]));
+            rs[qb] += p0;
+            rs[qb] += p1;
+            uint32_t wd = __builtin_bit_cast(uint32_t, __builtin_convertvector(v2f{p0, p1}, v2h));
+            asm volatile("" : "+v"(wd), "+v"(rs[qb]));     // keep the pass in place
+            reinterpret_cast<uint32_t*>(&pop[qb][b >> 1].u)[(b & 1) * 2 + h] = wd;
+        };
+        if (!LAST) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+            for (int j = 0; j < 3; ++j) ring[j].u = k_operand(j);
+        }
+        constexpr int V_STEPS = NB >= 2 ? NB / 2 : 1;      // V's copies are issued in the first half
+        constexpr int V_PER_STEP = CPT / V_STEPS;
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                _Float16 ph[4];
+        for (int b = 0; b <= NB; ++b) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float p = fast_exp2(__builtin_fmaf(s[qb][b][r], sc, cm[qb]));
-                    rs[qb] += p;
-                    ph[r] = (_Float16)p;
+            for (int ks = 0; ks < 4; ++ks) {
+                const int j = (b - 1) * 4 + ks;            // the pair that refills block b - 1
+                const bool mfma = !LAST && b >= 1;
+                if (mfma) {
+                    if (j + 3 < NQK) ring[(j + 3) & 3].u = k_operand(j + 3);
+                    qk_pair_half(j, 0);
                 }
-                v2h lo = v2h{ph[0], ph[1]}, hi = v2h{ph[2], ph[3]};
-                uint32_t wlo = __builtin_bit_cast(uint32_t, lo), whi = __builtin_bit_cast(uint32_t, hi);
-                asm volatile("" : "+v"(wlo), "+v"(whi), "+v"(rs[qb]));   // keep the pass in place
-                uint32_t* dstw = reinterpret_cast<uint32_t*>(&pop[qb][b >> 1].u);
-                dstw[(b & 1) * 2 + 0] = wlo;
-                dstw[(b & 1) * 2 + 1] = whi;
-            }
-            if (!LAST) qk_block(b);
+                if (b < NB) phase2_valu(b, ks);
+                if (mfma) qk_pair_half(j, 1);
+                if (b < V_STEPS && ks == 0) {
 #pragma unroll
-            for (int c = b * DMA_PER_BLOCK; c < (b + 1) * DMA_PER_BLOCK && c < CPT; ++c)
-                stage_chunk(1, vsrc, c);
-            __builtin_amdgcn_sched_barrier(0);
+                    for (int c = b * V_PER_STEP; c < (b + 1) * V_PER_STEP; ++c) stage_chunk(1, vsrc, c);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
