@@ -128,6 +128,10 @@ size_t fps_num_groups(const fps_shape* shape);
  * or 0 on an invalid shape. */
 size_t fps_tile_slots(const fps_shape* shape);
 
+/* BS, the slots of one block (the unit the kernels stage and a workgroup's query rows): 128, or 32
+ * when a quantisation group has at most 96 tokens; TSP is a multiple of it.  0 on an invalid shape. */
+size_t fps_block_slots(const fps_shape* shape);
+
 /* Bytes of one packed tensor for the given precision (all B*heads): M*TSP*head_dim bytes for FP8,
  * twice that for BF16.  0 on an invalid shape. */
 size_t fps_packed_bytes(const fps_shape* shape, fps_precision prec);

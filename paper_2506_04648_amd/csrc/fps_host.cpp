@@ -175,6 +175,12 @@ size_t fps_tile_slots(const fps_shape* shape) {
     return (size_t)g.TSP;
 }
 
+size_t fps_block_slots(const fps_shape* shape) {
+    Geom g;
+    if (check_shape(shape, &g) != FPS_OK) return 0;
+    return (size_t)g.BS;
+}
+
 size_t fps_packed_bytes(const fps_shape* shape, fps_precision prec) {
     Geom g;
     if (check_shape(shape, &g) != FPS_OK) return 0;

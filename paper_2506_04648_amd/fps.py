@@ -25,7 +25,7 @@ LAYOUT_TILED, LAYOUT_RASTER = 0, 1
 EDGE_TRUNCATE, EDGE_SHIFT = 0, 1
 
 EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_num_groups", "fps_tile_slots",
-           "fps_packed_bytes",
+           "fps_block_slots", "fps_packed_bytes",
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
            "fps_quantize_raster",
            "fps_pack_tiles_bf16", "fps_pack_raster_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
@@ -79,6 +79,8 @@ def lib():
         L.fps_num_groups.argtypes = [ctypes.POINTER(Shape)]
         L.fps_tile_slots.restype = ctypes.c_size_t
         L.fps_tile_slots.argtypes = [ctypes.POINTER(Shape)]
+        L.fps_block_slots.restype = ctypes.c_size_t
+        L.fps_block_slots.argtypes = [ctypes.POINTER(Shape)]
         L.fps_packed_bytes.restype = ctypes.c_size_t
         L.fps_packed_bytes.argtypes = [ctypes.POINTER(Shape), ip]
         L.fps_tile_mask_host.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), vp,
@@ -99,7 +101,7 @@ def lib():
                                    ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, ip, vp, vp]
         for name in EXPORTS:
             if name not in ("fps_last_error", "fps_num_tiles", "fps_num_groups", "fps_tile_slots",
-                            "fps_packed_bytes"):
+                            "fps_block_slots", "fps_packed_bytes"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -284,10 +286,11 @@ def debug_scores_q8(shape: Shape, q8, k8, bh, u, v):
 
 
 def block_slots(shape: Shape) -> int:
-    """BS, the slots of one block: 128, or 32 when a scale group (the tile, or the quantisation
-    sub-tile if one is given) has at most 96 tokens."""
-    qs = (shape.Qt * shape.Qh * shape.Qw) or (shape.Tt * shape.Th * shape.Tw)
-    return 32 if qs <= 96 else 128
+    """BS, the slots of one block, as the library lays tensors out (128 or 32)."""
+    n = lib().fps_block_slots(ctypes.byref(shape))
+    if n == 0:
+        raise FpsError(FPS_ERR_INVALID_ARG, last_error())
+    return int(n)
 
 
 def debug_scores_block_q8(shape: Shape, q8, k8, bh, u, jq, v, jk, out=None):

@@ -104,13 +104,15 @@ def test_shape_validation():
                                        ((2, 7, 15), (1, 7, 5), 6, 384), ((2, 8, 16), (2, 8, 16), 1, 256)]:
         sh = fps.make_shape(2, (4, 16, 16), tile, qtile=qtile)
         assert fps.num_groups(sh) == fps.num_tiles(sh) * groups and fps.tile_slots(sh) == slots, (tile, qtile)
-    # the binding's statement of the block size agrees with the slot counts the library reports
+    # the block size the library reports: 32 for groups of at most 96 tokens, else 128, and the slot
+    # counts follow from it
     for tile in [(1, 4, 4), (3, 4, 4), (1, 8, 12), (1, 7, 15), (1, 8, 16), (6, 8, 8), (24, 32, 32)]:
         for qtile in [None, (1, 1, tile[2]), (1, tile[1], tile[2])]:
             sh = fps.make_shape(2, (4, 16, 16), tile, qtile=qtile)
             qs = (qtile or tile)[0] * (qtile or tile)[1] * (qtile or tile)[2]
             ns = tile[0] * tile[1] * tile[2] // qs
             bs = fps.block_slots(sh)
+            assert bs == (32 if qs <= 96 else 128), (tile, qtile)
             assert fps.tile_slots(sh) == ns * -(-qs // bs) * bs, (tile, qtile)
     assert fps.num_groups(fps.make_shape(2, (4, 16, 16), (2, 8, 16))) == 4
     assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (2, 8, 16), qtile=(1, 3, 16))) == 0   # 3 does not divide 8
@@ -119,6 +121,7 @@ def test_shape_validation():
     assert fps.num_tiles(fps.make_shape(2, (4, 16, 16), (33, 32, 32))) == 0   # 33792 tokens: too large
     assert "unsupported" in fps.last_error()
     assert fps.tile_slots(fps.make_shape(2, (4, 16, 16), (33, 32, 32))) == 0
+    assert L.fps_block_slots(ctypes.byref(fps.make_shape(2, (4, 16, 16), (33, 32, 32)))) == 0
     assert fps.num_tiles(fps.make_shape(0, (4, 16, 16), (2, 4, 4))) == 0
     assert L.fps_num_tiles(None) == 0
 
