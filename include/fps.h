@@ -203,6 +203,22 @@ int fps_debug_copy(const void* src, void* dst, size_t bytes, void* stream);
  * memory of workgroups*256 floats that receives one value per thread. */
 int fps_debug_mfma_rate(int workgroups, int iters, float* sink, void* stream);
 
+/* Debug: how matrix and vector instructions share a SIMD's issue port -- the bound of the attention
+ * kernels, whose softmax puts a dozen vector instructions beside every matrix instruction
+ * (Sec. 3.4 calls the kernel tensor-core bound; this measures what the chip allows).  The kernel
+ * loops `iters` times over 8 groups, a group being one matrix instruction (matrix_kind 0:
+ * v_mfma_f32_16x16x128_f8f6f4 on E4M3; 1: v_mfma_f32_16x16x32_bf16; 2: none;
+ * 3: v_mfma_f32_32x32x64_f8f6f4 on E4M3, twice the work of 0) followed by
+ * valu_per_mfma (one of 0 1 2 3 4 6 8 12 16 24 32) vector units (valu_kind 0: one v_fma_f32; 1: one
+ * v_exp_f32 plus one v_add_f32), with no memory traffic.  `workgroups` workgroups of 256 threads
+ * are launched, each reserving 1/workgroups_per_cu of a compute unit's LDS so that exactly that
+ * many share a SIMD per wave slot.  cycles (device, workgroups*4 entries) receives each wave's
+ * shader-clock count for the whole loop; sink (device, workgroups*256 floats) one value per
+ * thread. */
+int fps_debug_issue_mix(int matrix_kind, int valu_per_mfma, int valu_kind, int workgroups_per_cu,
+                        int workgroups, int iters, float* sink, unsigned long long* cycles,
+                        void* stream);
+
 /* Debug: the raw score accumulators sum_c qcode_ic * kcode_jc (before the s^Q s^K / sqrt(d)
  * dequantisation of Eq. 3) of query tile u and key tile v of head bh, computed with the same
  * matrix instruction as fps_attn_fwd; `scores` is device memory of TSP*TSP floats, [query][key]

@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
-SOURCES = ("fps_host.cpp", "fps_layout.hip", "fps_quantize.hip", "fps_attn.hip")
+SOURCES = ("fps_host.cpp", "fps_layout.hip", "fps_quantize.hip", "fps_attn.hip", "fps_issue_mix.hip")
 OUT = os.path.join(_HERE, "libfps.so")
 
 

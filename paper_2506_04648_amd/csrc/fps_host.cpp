@@ -323,6 +323,27 @@ int fps_debug_mfma_rate(int workgroups, int iters, float* sink, void* stream) {
     return launch_mfma_rate(workgroups, iters, sink, (hipStream_t)stream);
 }
 
+int fps_debug_issue_mix(int matrix_kind, int valu_per_mfma, int valu_kind, int workgroups_per_cu,
+                        int workgroups, int iters, float* sink, unsigned long long* cycles,
+                        void* stream) {
+    FPS_TRY(check_ptr(sink, "sink"));
+    FPS_TRY(check_ptr(cycles, "cycles"));
+    if (matrix_kind < 0 || matrix_kind > 3 || valu_kind < 0 || valu_kind > 1) {
+        set_error("matrix_kind must be 0 (E4M3 16x16x128), 1 (bf16), 2 (none) or 3 (E4M3 32x32x64); valu_kind 0 (fma) or 1 (exp2)");
+        return FPS_ERR_INVALID_ARG;
+    }
+    if (workgroups_per_cu < 1 || workgroups_per_cu > 8) {
+        set_error("workgroups_per_cu must be in 1..8");
+        return FPS_ERR_INVALID_ARG;
+    }
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24)) {
+        set_error("workgroups must be in 1..2^20 and iters in 1..2^24");
+        return FPS_ERR_INVALID_ARG;
+    }
+    return launch_issue_mix(matrix_kind, valu_per_mfma, valu_kind, workgroups_per_cu, workgroups, iters,
+                            sink, cycles, (hipStream_t)stream);
+}
+
 int fps_debug_scores_q8(const fps_shape* shape, const void* q, const void* k, int bh, int u, int v,
                         float* scores, void* stream) {
     Geom g;

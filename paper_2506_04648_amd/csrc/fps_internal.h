@@ -100,6 +100,8 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
 
 int launch_copy(const void* in, void* out, long long bytes, hipStream_t st);
 int launch_mfma_rate(int workgroups, int iters, float* sink, hipStream_t st);
+int launch_issue_mix(int kind, int nv, int op, int workgroups_per_cu, int workgroups, int iters,
+                     float* sink, unsigned long long* cycles, hipStream_t st);
 int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int v, float* out,
                       hipStream_t st);
 int launch_scores_block_fp8(const Geom& g, const void* q, const void* k, int bh, int u, int jq, int v,

@@ -29,7 +29,7 @@ EXPORTS = ("fps_last_error", "fps_schedule_select", "fps_num_tiles", "fps_num_gr
            "fps_tile_mask_host", "fps_tile_order", "fps_tile_unorder", "fps_quantize_tiles",
            "fps_quantize_raster",
            "fps_pack_tiles_bf16", "fps_pack_raster_bf16", "fps_debug_unpack_q8", "fps_debug_copy", "fps_debug_scores_q8",
-           "fps_debug_scores_block_q8", "fps_debug_mfma_rate",
+           "fps_debug_scores_block_q8", "fps_debug_mfma_rate", "fps_debug_issue_mix",
            "fps_attn_fwd")
 
 
@@ -97,6 +97,7 @@ def lib():
         L.fps_debug_scores_block_q8.argtypes = [ctypes.POINTER(Shape), vp, vp, ip, ip, ip, ip, ip, vp,
                                                 ctypes.POINTER(ctypes.c_int), vp]
         L.fps_debug_mfma_rate.argtypes = [ip, ip, vp, vp]
+        L.fps_debug_issue_mix.argtypes = [ip, ip, ip, ip, ip, ip, vp, vp, vp]
         L.fps_attn_fwd.argtypes = [ctypes.POINTER(Shape), ctypes.POINTER(Window), ip,
                                    ctypes.POINTER(StepCfg), vp, vp, vp, vp, vp, vp, ip, vp, ip, ip, vp, vp]
         for name in EXPORTS:
@@ -274,6 +275,13 @@ def debug_mfma_rate(workgroups, iters, sink):
     assert sink.is_cuda and sink.numel() >= workgroups * 256
     _check(lib().fps_debug_mfma_rate(workgroups, iters, _ptr(sink), _stream()))
     return workgroups * 4 * iters * 8 * 65536.0
+
+
+def debug_issue_mix(matrix_kind, valu_per_mfma, valu_kind, workgroups_per_cu, workgroups, iters, sink, cycles):
+    """One launch of the matrix/vector issue-mix kernel; cycles (int64, workgroups*4) receives each
+    wave's shader clocks for iters*8 groups."""
+    _check(lib().fps_debug_issue_mix(matrix_kind, valu_per_mfma, valu_kind, workgroups_per_cu, workgroups,
+                                     iters, _ptr(sink), _ptr(cycles), _stream()))
 
 
 def debug_scores_q8(shape: Shape, q8, k8, bh, u, v):

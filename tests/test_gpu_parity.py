@@ -458,6 +458,29 @@ def test_mfma_rate_kernel_runs():
     assert torch.equal(b, 2 * a)
 
 
+def test_issue_mix_kernel_counts_shader_clocks():
+    """The matrix/vector issue-mix micro-benchmark: every wave reports a clock count, and an
+    MFMA-only loop of the E4M3 16x16x128 instruction takes its 8 passes (32 clocks) per instruction
+    on a SIMD that holds one wave."""
+    import torch
+    say("issue mix")
+    wgs, iters = 8, 200
+    sink = torch.full((wgs * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
+    cyc = torch.zeros(wgs * 4, dtype=torch.int64, device="cuda:0")
+    fps.debug_issue_mix(0, 0, 0, 1, wgs, iters, sink, cyc)
+    torch.cuda.synchronize()
+    per_mfma = cyc.double() / (iters * 8)
+    assert torch.isfinite(sink).all() and (cyc > 0).all()
+    assert 30.0 <= float(per_mfma.min()) and float(per_mfma.max()) <= 40.0, per_mfma
+    for kind, nv, op in [(1, 4, 0), (2, 8, 1), (3, 16, 0)]:
+        cyc.zero_()
+        fps.debug_issue_mix(kind, nv, op, 2, wgs, iters, sink, cyc)
+        torch.cuda.synchronize()
+        assert (cyc > 0).all() and torch.isfinite(sink).all()
+    with pytest.raises(fps.FpsError):
+        fps.debug_issue_mix(0, 5, 0, 1, wgs, iters, sink, cyc)          # not one of the built group sizes
+
+
 def test_batch_and_heads_are_interchangeable():
     """Tensors are indexed by b*heads + h: (B=2, heads=3) equals (B=1, heads=6) bit for bit."""
     import torch
