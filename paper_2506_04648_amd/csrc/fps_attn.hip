@@ -53,6 +53,8 @@ struct MaskTables {
     // lane_mask[c][4b + r]: bit of lane (n, g) set iff the key that lane holds in accumulator slot
     // (block b, element r), slot 16b + 4g + r of a one-block tile, is a real token (class c)
     uint64_t lane_mask[8][32];
+    // 128-slot blocks (32x32 accumulators): see arg_pair_code
+    uint32_t pair_code[8][4];
 };
 constexpr size_t kTablesOffset = (sizeof(AttnArgs) + 7) & ~size_t(7);   // kernarg offset of MaskTables
 
@@ -651,6 +653,378 @@ void attn_fp8_kernel(AttnArgs a, MaskTables) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// FP8, 128-slot blocks: the same pipeline on v_mfma_f32_32x32x64_f8f6f4.  One instruction of 16
+// passes does the work of two 16x16x128 ones, and what an MFMA costs the vector instructions
+// around it is largely per instruction (measured with fps_debug_issue_mix: beside 32 vector
+// instructions one 32x32x64 adds 30 clocks, two 16x16x128 add 49), so the softmax's vector work
+// shares the SIMD with half as many matrix instructions.  A wave owns 32 query rows as ONE operand
+// block: lane (n, h) = lane & 31, lane >> 5 holds query n; of a 32-key score block kb it holds the
+// keys 8(r/4) + 4h + r%4, r = 0..15; of a 32-channel output block db the channels of the same
+// pattern.  The other lane of the row is lane n + 32.
+// ---------------------------------------------------------------------------------------------
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ v16f zero16() {
+    v16f z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+    return z;
+}
+__device__ __forceinline__ float max_over_row_pair(float t) {          // lanes n and n + 32
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    return __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_over_row_pair(float t) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// pair_code[c][kb], bits 2r + h: set iff the key that lane half h holds in register r of score block
+// kb, slot 32kb + 8(r/4) + 4h + r%4 of a one-block tile of class c, is a real token
+__device__ __forceinline__ uint32_t arg_pair_code(int cls, int kb) {
+    typedef const __attribute__((address_space(4))) uint32_t* ptr_t;
+    const __attribute__((address_space(4))) char* base =
+        (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
+    return ((ptr_t)(base + kTablesOffset + offsetof(MaskTables, pair_code)))[cls * 4 + kb];
+}
+// the wave-wide lane mask of register r: all of a lane half, or none of it
+__device__ __forceinline__ uint64_t pair_lane_mask(uint32_t code, int r) {
+    const uint32_t c2 = code >> (2 * r);
+    return (uint64_t)(uint32_t)(-(int)(c2 & 1u)) | ((uint64_t)(uint32_t)(-(int)((c2 >> 1) & 1u)) << 32);
+}
+
+// Epilogue of the wide kernel: as store_rows, for accumulators of the 32x32 shape.  The wave's 32
+// rows go through its LDS region in two passes of 16 rows (rows n < 16 are held by lanes 0..15 and
+// 32..47).
+__device__ __forceinline__ void store_rows_wide(const AttnArgs& a, int bh, int u, int jq, int KBS, int ucls,
+                                                int wave, int lane, const v16f (&acc)[4], float inv,
+                                                uint8_t* wave_lds, const float* ch_scale = nullptr) {
+    constexpr int BS = 128;
+    const auto& G = a.g;
+    const int h = lane >> 5, n = lane & 31;
+    const int row_bytes = a.out_f32 ? 512 : 256;
+    const int pitch = row_bytes + 16;
+    const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
+    const int sub = jq / KBS;
+    const SubTile so = sub_tile_origin(G, sub);
+    const int slot0 = (jq - sub * KBS) * BS;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        if ((n >> 4) == pass) {
+            const int rr = n & 15;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int col = 32 * db + 8 * q4 + 4 * h;
+                    v4f o = v4f{acc[db][4 * q4], acc[db][4 * q4 + 1], acc[db][4 * q4 + 2], acc[db][4 * q4 + 3]} * inv;
+                    if (ch_scale) o *= *reinterpret_cast<const v4f*>(ch_scale + col);
+                    if (a.out_f32) {
+                        *reinterpret_cast<v4f*>(wave_lds + rr * pitch + col * 4) = o;
+                    } else {
+                        uint2 pk;
+                        pk.x = pack_bf16x2(o[0], o[1]);
+                        pk.y = pack_bf16x2(o[2], o[3]);
+                        *reinterpret_cast<uint2*>(wave_lds + rr * pitch + col * 2) = pk;
+                    }
+                }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int lanes_shift = a.out_f32 ? 5 : 4;
+        const int rows_per_pass = 64 >> lanes_shift;
+        for (int r0 = 0; r0 < 16; r0 += rows_per_pass) {
+            const int r = r0 + (lane >> lanes_shift), chunk = lane & ((1 << lanes_shift) - 1);
+            const int in_block = wave * 32 + pass * 16 + r;
+            int rt = 0, rh = 0, rw = 0;
+            const bool valid = sub_slot_coords(G, so, slot0 + in_block, &rt, &rh, &rw) &&
+                               coords_in_class(G, ucls, rt, rh, rw);
+            uint4 val = *reinterpret_cast<const uint4*>(wave_lds + r * pitch + chunk * 16);
+            size_t row;
+            if (a.out_raster) {
+                if (!valid) continue;
+                row = (((size_t)bh * G.T + (ut * G.Tt + rt)) * G.H + (uh * G.Th + rh)) * G.W + (uw * G.Tw + rw);
+            } else {
+                row = ((size_t)bh * G.M + u) * G.TSP + (size_t)jq * BS + in_block;
+                if (!valid) val = make_uint4(0, 0, 0, 0);
+            }
+            reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(a.out) + row * row_bytes)[chunk] = val;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <bool VCH, bool MB, int NK>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_fp8_wide_kernel(AttnArgs a, MaskTables) {
+    constexpr int BS = 128;
+    constexpr int NTHR = 256;
+    constexpr int CPT = (BS * 8) / NTHR;                   // 16-byte chunks per thread per operand tile (4)
+    constexpr int TILE_BYTES = BS * 128;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[4][TILE_BYTES];   // K even, K odd, V even, V odd
+    const Geom& G = a.g;
+    const int KB = MB ? G.KB : 1;
+    const int KB_LAST = MB ? G.kb_last : 1;
+    const int KBS = MB ? G.KBS : 1;
+    const int NS = MB ? G.NS : 1;
+    int bh, u, jq;
+    if (!work_item(a, KB, &bh, &u, &jq)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, n = lane & 31;
+    const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
+    if (MB && jq >= (ut == G.nT - 1 ? KB_LAST : KB)) {      // a query block of padding only
+        zero_block_rows<BS, NTHR>(a, bh, u, jq);
+        return;
+    }
+    const size_t tile0 = (size_t)bh * G.M;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(&lds[0][0]);
+
+    v8i qop[2];                                            // Q^T, contraction steps 0 and 1
+    float m_run = -INFINITY;
+    float l_run = 0.f;                                     // running sum of 448 * P (this lane's keys)
+    float alpha_prev = 1.f;                                // VCH: rescale owed to O before the delayed PV
+    float m_base = 0.f, w_cur = 1.f, w_prev = 0.f;         // fixed reference and weights: see attn_fp8_kernel
+    v16f acc[4];
+    {
+        const int row = wave * 32 + n;
+        const uint4* p = reinterpret_cast<const uint4*>(
+            a.q + (((tile0 + u) * KB + jq) * BS + row) * 128 + 32 * h);
+        qop[0] = make_v8i(p[0], p[1]);
+        qop[1] = make_v8i(p[4], p[5]);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) acc[db] = zero16();
+    }
+    const float sqc = load_uniform(a.sq, (tile0 + u) * NS + jq / KBS) * kLog2eOverSqrtD;
+
+    TileWalk w0, w2;
+    w0.init(a, KB, KB_LAST, KBS, ut, uh, uw);
+    w2 = w0;
+    const int ntiles = w0.n;
+    auto tile_of = [&](const TileWalk& w) FPS_INLINE { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {
+        dma_chunk_of(c, src + wave_s * (CPT * 1024), lane * 16, lds_base + buf * TILE_BYTES + wave_s * (CPT * 1024));
+    };
+    auto stage = [&](int buf, const uint8_t* src) FPS_INLINE {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) stage_chunk(buf, src, c);
+    };
+    auto k_blk = [&](const TileWalk& w) FPS_INLINE { return a.k + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
+    auto v_blk = [&](const TileWalk& w) FPS_INLINE { return a.v + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
+
+    v16f s[4];                                             // S^T, four blocks of 32 keys
+    v8i pb[2];                                             // P^T as packed E4M3: contraction steps 0 and 1
+    pb[0] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+    pb[1] = pb[0];
+
+    // operand `step` (block * 2 + contraction step) of a staged K or V block
+    auto load_op = [&](const uint8_t* buf, int step) FPS_INLINE {
+        const uint4* b4 = reinterpret_cast<const uint4*>(buf);
+        return make_v8i(b4[(step * 2 + 0) * 64 + lane], b4[(step * 2 + 1) * 64 + lane]);
+    };
+    auto qk_mfma = [&](const v8i& kop, int step) FPS_INLINE {
+        const int kb = step >> 1, ks = step & 1;
+        s[kb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kop, qop[ks], ks == 0 ? zero16() : s[kb],
+                                                               0, 0, 0, 0, 0, 0);
+    };
+    v16f tq[2];                                            // raw V^T P^T of a channel block, until its fma
+    auto pv_mfma = [&](const v8i& vop, int step) FPS_INLINE {
+        const int db = step >> 1, j = step & 1;
+        if (VCH) acc[db] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vop, pb[j], acc[db], 0, 0, 0, 0, 0, 0);
+        else     tq[db & 1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                     vop, pb[j], j == 0 ? zero16() : tq[db & 1], 0, 0, 0, 0, 0, 0);
+    };
+    // half `half` of O^T(db) += s^V 2^(m - m_base) * raw, pinned where it is written
+    auto pv_accumulate_half = [&](int db, int half) FPS_INLINE {
+        if (VCH) return;
+#pragma unroll
+        for (int r = 8 * half; r < 8 * half + 8; ++r) acc[db][r] = __builtin_fmaf(tq[db & 1][r], w_prev, acc[db][r]);
+        asm volatile("" : "+v"(acc[db]));
+    };
+    auto mask_scores = [&](int cls, int js, int jb) FPS_INLINE {      // padded keys of a boundary tile: -inf
+        cls = __builtin_amdgcn_readfirstlane(cls);
+        if (!((a.partial_cls >> cls) & 1u)) return;
+        if (!MB) {
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                const uint32_t code = arg_pair_code(cls, kb);          // uniform: one scalar load
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    s[kb][r] = select_lanes(pair_lane_mask(code, r), s[kb][r], -INFINITY);
+            }
+        } else {
+            uint64_t bm[2];
+            block_ballots<BS>(G, cls, js, jb, lane, bm);
+            if ((bm[0] & bm[1]) == ~0ull) return;          // most blocks of a boundary tile are whole
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                const uint32_t bits = (uint32_t)(bm[kb >> 1] >> (32 * (kb & 1))) >> (4 * h);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (!((bits >> (8 * (r >> 2) + (r & 3))) & 1u)) s[kb][r] = -INFINITY;
+            }
+        }
+    };
+    auto rescale_acc = [&]() FPS_INLINE {                             // VCH only
+        if (!VCH) return;
+        if (__any(alpha_prev != 1.0f)) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db) acc[db] *= alpha_prev;
+        }
+    };
+
+    // prologue: K(0), K(1) staged; S(0) computed
+    stage(0, k_blk(w2));
+    w2.next();
+    if (ntiles > 1) { stage(1, k_blk(w2)); w2.next(); }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int step = 0; step < 8; ++step) qk_mfma(load_op(lds[0], step), step);
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
+
+    float sc_next = sqc * load_uniform(a.sk, (tile0 + tile_of(w0)) * NS + w0.js);
+    float sv_next = VCH ? 1.f : load_uniform(a.sv, (tile0 + tile_of(w0)) * NS + w0.js);
+    auto iteration = [&](auto first_tag, auto last_tag, int it) FPS_INLINE {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        constexpr bool LAST = decltype(last_tag)::value;
+        const int par = it & 1;
+        const uint8_t* knxt = lds[par ^ 1];                // K(i+1)
+        const uint8_t* vprev = lds[2 + (par ^ 1)];         // V(i-1)
+        const int v = tile_of(w0);
+        const float sc = sc_next;
+        const float svv = sv_next;
+        if (a.visited && bh == 0 && tid == 0 && jq == 0 && w0.jk == 0) a.visited[(size_t)u * G.M + v] = 1;
+        __syncthreads();                 // every wave is past QK(i) and PV(i-2); staged tiles are visible
+        v8i op[3];                       // MFMA operands on their way from LDS, two steps ahead
+        if (!FIRST) { op[0] = load_op(vprev, 0); op[1] = load_op(vprev, 1); }
+        const bool fetch_k = it + 2 < ntiles;
+        const uint8_t* ksrc = fetch_k ? k_blk(w2) : nullptr;
+        const uint8_t* vsrc = v_blk(w0);
+        if (fetch_k) w2.next();
+        w0.next();
+        if (!LAST) {                     // scales of tile i+1, needed next iteration
+            const size_t gn = (tile0 + tile_of(w0)) * NS + w0.js;
+            sc_next = sqc * load_uniform(a.sk, gn);
+            if (!VCH) sv_next = load_uniform(a.sv, gn);
+        }
+
+        // ---- phase 1: row maximum of S(i)  |  delayed PV(i-1) --------------------------------
+        // step k: half the fma of the block whose second MFMA was issued two or three steps earlier
+        // (a 16-pass result may be read 18 issue slots after its instruction), the MFMA of channel
+        // block k/2, contraction step k%2, and an eighth of the row maximum
+        if (!FIRST) rescale_acc();
+        float mx = __builtin_fmaxf(__builtin_fmaxf(s[0][0], s[0][1]), __builtin_fmaxf(s[0][2], s[0][3]));
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (!FIRST) {
+                if (k + 2 < 8) op[(k + 2) % 3] = load_op(vprev, k + 2);
+                if (k >= 3) pv_accumulate_half((k - 3) >> 1, (k - 3) & 1);   // before tq[..] is refilled
+                pv_mfma(op[k % 3], k);
+            }
+#pragma unroll
+            for (int r = (k == 0 ? 4 : 8 * (k & 1)); r < 8 * (k & 1) + 8; r += 2)
+                mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[k >> 1][r]), s[k >> 1][r + 1]);
+            asm volatile("" : "+v"(mx));
+            if (k < CPT) stage_chunk(2 + par, vsrc, k);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (!FIRST) pv_accumulate_half(2, 1);
+        if (!LAST) { op[0] = load_op(knxt, 0); op[1] = load_op(knxt, 1); }   // K(i+1): visible since the barrier
+        mx = max_over_row_pair(mx);
+        const float m_new = __builtin_fmaxf(m_run, __builtin_ceilf(mx * sc));
+        if (VCH) {
+            alpha_prev = fast_exp2(m_run - m_new);
+        } else {
+            if (FIRST) m_base = m_new;
+            w_cur = fast_exp2(m_new - m_base);
+        }
+        m_run = m_new;
+        const float cm = kLog2Of448 - m_new;   // 448 * 2^(S' - m) = 2^(S' + (log2(448) - m))
+        if (!VCH && !FIRST && __any(m_run - m_base > kMaxDrift)) {
+            const float down = fast_exp2(m_base - m_run);
+#pragma unroll
+            for (int db = 0; db < 4; ++db) acc[db] *= down;
+            l_run *= down;
+            w_prev *= down;              // the last channel block's fma is still owed (steps 0, 1 below)
+            m_base = m_run;
+            w_cur = 1.0f;
+        }
+
+        // ---- phase 2: P(i) and its FP8 codes  |  early QK(i+1) ------------------------------
+        // step t: the exponentials of half a score block (block t/2, registers 8(t%2)..+7); the
+        // MFMAs that refill a block follow one block behind, so steps 0, 1 have none (they take the
+        // fma still owed to the last channel block of PV(i-1)) and steps 8, 9 nothing else
+        float rs = 0.f;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 10; ++t) {
+            if (!LAST && t >= 2) {
+                if (t < 8) op[t % 3] = load_op(knxt, t);               // operand of step t + 2
+                qk_mfma(op[(t - 2) % 3], t - 2);
+            }
+            if (!FIRST && t < 2) pv_accumulate_half(3, t);             // PV(i-1)'s last block
+            if (t < 8) {
+                const int kb = t >> 1, e = t & 1;
+#pragma unroll
+                for (int q2 = 0; q2 < 2; ++q2) {
+                    float p[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        p[r] = fast_exp2(__builtin_fmaf(s[kb][8 * e + 4 * q2 + r], sc, cm));
+                        rs += p[r];
+                    }
+                    int pw = pb[kb >> 1][4 * (kb & 1) + 2 * e + q2];
+                    pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], pw, false);
+                    pw = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], pw, true);
+                    asm volatile("" : "+v"(pw), "+v"(rs));  // keep the pass where it is written
+                    pb[kb >> 1][4 * (kb & 1) + 2 * e + q2] = pw;
+                }
+            }
+            if (t < CPT && fetch_k) stage_chunk(par, ksrc, t);   // K(i) was consumed last iteration
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (VCH) l_run = l_run * alpha_prev + rs;
+        else     l_run = __builtin_fmaf(rs, w_cur, l_run);
+        w_prev = svv * w_cur;
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's share of the staged tiles landed
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    if constexpr (NK == kOneKeyBlock) {
+        iteration(T_{}, T_{}, 0);
+    } else if constexpr (NK == kManyKeyBlocks) {
+        iteration(T_{}, F_{}, 0);
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{}, it);
+        iteration(F_{}, T_{}, ntiles - 1);
+    } else if (ntiles == 1) {
+        iteration(T_{}, T_{}, 0);
+    } else {
+        iteration(T_{}, F_{}, 0);
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{}, it);
+        iteration(F_{}, T_{}, ntiles - 1);
+    }
+    // epilogue: the last tile's PV
+    __syncthreads();
+    rescale_acc();
+    {
+        const uint8_t* vlast = lds[2 + ((ntiles - 1) & 1)];
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            pv_mfma(load_op(vlast, 2 * db), 2 * db);
+            pv_mfma(load_op(vlast, 2 * db + 1), 2 * db + 1);
+            pv_accumulate_half(db, 0);
+            pv_accumulate_half(db, 1);
+        }
+    }
+    const float l = sum_over_row_pair(l_run);
+    const float inv = l > 0.f ? 1.0f / l : 0.f;            // l already carries the factor 448
+    __syncthreads();                                       // all waves are done with the staged tiles
+    store_rows_wide(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+                    &lds[0][0] + wave * kStoreRegionBytes, VCH ? a.sv + (size_t)bh * 128 : nullptr);
+}
+
+// ---------------------------------------------------------------------------------------------
 // BF16: no quantisation.  K Q^T on v_mfma_f32_16x16x32_bf16; P is rounded to fp16 and multiplied
 // with the fp16 V tiles (exact per-tile power-of-two scaling, undone by s^V) on
 // v_mfma_f32_16x16x32_f16.  Same in-wave pipeline as the FP8 kernel (PV one tile late, QK one tile
@@ -1010,6 +1384,31 @@ __global__ __launch_bounds__(BS * 2) void scores_fp8_kernel(const uint8_t* __res
     }
 }
 
+// The same for 128-slot blocks: the 32x32x64 instruction and operand layouts of attn_fp8_wide_kernel.
+__global__ __launch_bounds__(256) void scores_fp8_wide_kernel(const uint8_t* __restrict__ q_tile,
+                                                              const uint8_t* __restrict__ k_tile,
+                                                              float* __restrict__ out_tile, int out_pitch) {
+    const uint8_t* q = q_tile + (size_t)blockIdx.y * 128 * 128;
+    const uint8_t* k = k_tile + (size_t)blockIdx.x * 128 * 128;
+    float* out = out_tile + (size_t)blockIdx.y * 128 * out_pitch + (size_t)blockIdx.x * 128;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, n = lane & 31;
+    const uint4* k4 = reinterpret_cast<const uint4*>(k);
+    const int row = wave * 32 + n;
+    const uint4* p = reinterpret_cast<const uint4*>(q + row * 128 + 32 * h);
+    const v8i qop[2] = {make_v8i(p[0], p[1]), make_v8i(p[4], p[5])};
+    for (int kb = 0; kb < 4; ++kb) {
+        v16f s = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const v8i kop = make_v8i(k4[((kb * 2 + ks) * 2 + 0) * 64 + lane], k4[((kb * 2 + ks) * 2 + 1) * 64 + lane]);
+            s = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kop, qop[ks], s, 0, 0, 0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            out[(size_t)row * out_pitch + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3)] = s[r];
+    }
+}
+
 // MFMA-only loop: 8 independent accumulator chains of the attention kernel's matrix instruction.
 __global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ sink, int iters, int x) {
     v8i a = {x, x, x, x, x, x, x, x};
@@ -1041,7 +1440,7 @@ int launch_scores_fp8(const Geom& g, const void* q, const void* k, int bh, int u
     const uint8_t* qp = (const uint8_t*)q + ((size_t)bh * g.M + u) * tile_bytes;
     const uint8_t* kp = (const uint8_t*)k + ((size_t)bh * g.M + v) * tile_bytes;
     const dim3 grid(g.KB, g.KB);
-    if (g.BS == 128) scores_fp8_kernel<128><<<grid, 256, 0, st>>>(qp, kp, out, g.TSP);
+    if (g.BS == 128) scores_fp8_wide_kernel<<<grid, 256, 0, st>>>(qp, kp, out, g.TSP);
     else             scores_fp8_kernel<32><<<grid, 64, 0, st>>>(qp, kp, out, g.TSP);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "debug scores launch");
@@ -1052,7 +1451,7 @@ int launch_scores_block_fp8(const Geom& g, const void* q, const void* k, int bh,
     const size_t blk_bytes = (size_t)g.BS * 128;
     const uint8_t* qp = (const uint8_t*)q + (((size_t)bh * g.M + u) * g.KB + jq) * blk_bytes;
     const uint8_t* kp = (const uint8_t*)k + (((size_t)bh * g.M + v) * g.KB + jk) * blk_bytes;
-    if (g.BS == 128) scores_fp8_kernel<128><<<dim3(1, 1), 256, 0, st>>>(qp, kp, out, g.BS);
+    if (g.BS == 128) scores_fp8_wide_kernel<<<dim3(1, 1), 256, 0, st>>>(qp, kp, out, g.BS);
     else             scores_fp8_kernel<32><<<dim3(1, 1), 64, 0, st>>>(qp, kp, out, g.BS);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "debug block scores launch");
@@ -1090,6 +1489,10 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
                     if (ok[16 * b + 4 * (lane >> 4) + r]) m |= 1ull << lane;
                 t.lane_mask[c][i] = m;
             }
+            for (int kb = 0; kb < 4; ++kb)
+                for (int r = 0; r < 16; ++r)
+                    for (int h = 0; h < 2; ++h)
+                        if (ok[32 * kb + 8 * (r >> 2) + 4 * h + (r & 3)]) t.pair_code[c][kb] |= 1u << (2 * r + h);
         }
     }
     const int grid = a.chunk * 8;
@@ -1102,22 +1505,24 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     const bool one = corner == 1;
     // tiles of several blocks: a lower bound on the key blocks of any item
     const bool many = (long long)corner * (g.KB < g.kb_last ? g.KB : g.kb_last) >= 2;
-#define FPS_LAUNCH_FP8(BS_, THREADS_)                                                              \
+#define FPS_LAUNCH_FP8(KERNEL_, THREADS_)                                                          \
     do {                                                                                           \
         if (multi && many) {                                                                       \
-            if (vch) attn_fp8_kernel<BS_, true, true, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);       \
-            else     attn_fp8_kernel<BS_, false, true, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);      \
+            if (vch) KERNEL_(true, true, kManyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);         \
+            else     KERNEL_(false, true, kManyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);        \
         } else if (multi) {                                                                        \
-            if (vch) attn_fp8_kernel<BS_, true, true, kAnyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);        \
-            else     attn_fp8_kernel<BS_, false, true, kAnyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);       \
+            if (vch) KERNEL_(true, true, kAnyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);          \
+            else     KERNEL_(false, true, kAnyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);         \
         } else if (one) {                                                                          \
-            if (vch) attn_fp8_kernel<BS_, true, false, kOneKeyBlock><<<grid, THREADS_, 0, st>>>(a, t);        \
-            else     attn_fp8_kernel<BS_, false, false, kOneKeyBlock><<<grid, THREADS_, 0, st>>>(a, t);       \
+            if (vch) KERNEL_(true, false, kOneKeyBlock)<<<grid, THREADS_, 0, st>>>(a, t);          \
+            else     KERNEL_(false, false, kOneKeyBlock)<<<grid, THREADS_, 0, st>>>(a, t);         \
         } else {                                                                                   \
-            if (vch) attn_fp8_kernel<BS_, true, false, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);      \
-            else     attn_fp8_kernel<BS_, false, false, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t);     \
+            if (vch) KERNEL_(true, false, kManyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);        \
+            else     KERNEL_(false, false, kManyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);       \
         }                                                                                          \
     } while (0)
+#define FPS_FP8_WIDE(VCH_, MB_, NK_) attn_fp8_wide_kernel<VCH_, MB_, NK_>
+#define FPS_FP8_SMALL(VCH_, MB_, NK_) attn_fp8_kernel<32, VCH_, MB_, NK_>
 #define FPS_LAUNCH_BF16(BS_, THREADS_)                                                             \
     do {                                                                                           \
         if (multi && many) attn_bf16_kernel<BS_, true, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
@@ -1126,11 +1531,13 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
         else          attn_bf16_kernel<BS_, false, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
     } while (0)
     if (prec == FPS_PREC_FP8) {
-        if (g.BS == 128) FPS_LAUNCH_FP8(128, 256); else FPS_LAUNCH_FP8(32, 64);
+        if (g.BS == 128) FPS_LAUNCH_FP8(FPS_FP8_WIDE, 256); else FPS_LAUNCH_FP8(FPS_FP8_SMALL, 64);
     } else {
         if (g.BS == 128) FPS_LAUNCH_BF16(128, 256); else FPS_LAUNCH_BF16(32, 64);
     }
 #undef FPS_LAUNCH_FP8
+#undef FPS_FP8_WIDE
+#undef FPS_FP8_SMALL
 #undef FPS_LAUNCH_BF16
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "attention launch");

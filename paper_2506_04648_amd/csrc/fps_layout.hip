@@ -2,17 +2,24 @@
 // and the debug unpacking of packed E4M3 tensors.  All of them are pure data movement.
 //
 // Packed operand layouts, per block of BS = 128 or 32 slots (a tile is one or several blocks).
-// "lane" = 16*g + n is the MFMA lane that consumes the chunk: n selects the row of the 16-row
-// operand block, g the group of contraction slots.
-//   E4M3 Q : row-major [token][128]                                    (BS*128 bytes)
-//   E4M3 K : 16-byte chunk ((b*2 + h)*64 + lane) = K[16b + n][32g + 16h + 0..15]
-//   E4M3 V : BS=128: 16-byte chunk ((cb*2 + h)*64 + lane), byte j -> slot s = 16h + j
-//            BS=32 :  8-byte chunk (cb*64 + lane),          byte j -> slot s = j
-//            holding V[key(g,s)][16cb + n] with key(g,s) = 16*(s/4) + 4g + s%4
-//   BF16 Q : row-major [token][128]                                    (BS*256 bytes)
-//   BF16 K : 16-byte chunk ((b*4 + ks)*64 + lane) = K[16b + n][32ks + 8g + 0..7]
-//   BF16 V : 16-byte chunk ((kk*8 + cb)*64 + lane), element e -> V[32kk + key(g,e)][16cb + n],
-//            stored as fp16 after an exact power-of-two scaling per scale group (see pack_bf16_kernel)
+// E4M3, BS = 128 -- operands of v_mfma_f32_32x32x64_f8f6f4; lane = 32h + n, n the row of the 32-row
+// operand block, h the half of the 64 contraction slots of one step:
+//   Q : row-major [token][128]                                              (BS*128 bytes)
+//   K : 16-byte chunk (((kb*2 + ks)*2 + e)*64 + lane) = K[32kb + n][64ks + 32h + 16e + 0..15]
+//   V : 16-byte chunk (((db*2 + j)*2 + e)*64 + lane), byte jj = V[key][32db + n] with
+//       key = 32(2j + e) + 8(jj/4) + 4h + jj%4
+//   The accumulator of S^T = K Q^T for key block kb holds, in lane (n,h) and register r, query n and
+//   key 32kb + 8(r/4) + 4h + r%4; the 32 weights of key blocks 2j and 2j+1 of a lane are therefore,
+//   unchanged, its 32 contraction slots of step j of the PV product O^T = V^T P^T.
+// E4M3, BS = 32 -- operands of the 16x16 instructions; lane = 16g + n:
+//   Q : row-major [token][128]
+//   K : 16-byte chunk ((b*2 + h)*64 + lane) = K[16b + n][32g + 16h + 0..15]
+//   V :  8-byte chunk (cb*64 + lane), byte j = V[key(g,j)][16cb + n], key(g,s) = 16*(s/4) + 4g + s%4
+// BF16 (both block sizes), 16x16x32 instructions; lane = 16g + n:
+//   Q : row-major [token][128]                                              (BS*256 bytes)
+//   K : 16-byte chunk ((b*4 + ks)*64 + lane) = K[16b + n][32ks + 8g + 0..7]
+//   V : 16-byte chunk ((kk*8 + cb)*64 + lane), element e -> V[32kk + key(g,e)][16cb + n],
+//       stored as fp16 after an exact power-of-two scaling per scale group (see pack_bf16_kernel)
 // key(g,s) is the key that slot s of lane group g holds after a 16x16 MFMA wrote S^T = K Q^T: the
 // accumulator of lane (n,g) for key block b has keys 16b + 4g + 0..3, so P^T can be fed back as
 // the second operand of the PV product without any cross-lane movement.
@@ -145,13 +152,21 @@ __global__ __launch_bounds__(256) void unpack_q8_kernel(const uint8_t* __restric
         if (role == FPS_ROLE_Q) {
             off = i;
         } else if (role == FPS_ROLE_K) {
-            const int b = j >> 4, n = j & 15, gg = c >> 5, h = (c >> 4) & 1;
-            off = ((b * 2 + h) * 64 + gg * 16 + n) * 16 + (c & 15);
+            if (BS == 128) {
+                const int kb = j >> 5, n = j & 31, ks = c >> 6, h = (c >> 5) & 1, e = (c >> 4) & 1;
+                off = (((kb * 2 + ks) * 2 + e) * 64 + 32 * h + n) * 16 + (c & 15);
+            } else {
+                const int b = j >> 4, n = j & 15, gg = c >> 5, h = (c >> 4) & 1;
+                off = ((b * 2 + h) * 64 + gg * 16 + n) * 16 + (c & 15);
+            }
+        } else if (BS == 128) {                            // inverse of the wide key order
+            const int db = c >> 5, n = c & 31;
+            const int kb = j >> 5, rem = j & 31, h = (rem >> 2) & 1, jj = 4 * (rem >> 3) + (rem & 3);
+            off = (((db * 2 + (kb >> 1)) * 2 + (kb & 1)) * 64 + 32 * h + n) * 16 + jj;
         } else {
             const int cb = c >> 4, n = c & 15;
             const int gg = (j >> 2) & 3, s = 4 * (j >> 4) + (j & 3);   // inverse of key_of_slot
-            if (BS == 128) off = ((cb * 2 + (s >> 4)) * 64 + gg * 16 + n) * 16 + (s & 15);
-            else           off = (cb * 64 + gg * 16 + n) * 8 + s;
+            off = (cb * 64 + gg * 16 + n) * 8 + s;
         }
         dst[i] = src[off];
     }

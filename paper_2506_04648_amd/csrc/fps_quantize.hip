@@ -7,6 +7,11 @@
 namespace fps {
 
 __device__ __forceinline__ int key_of_slot_q(int g, int s) { return 16 * (s >> 2) + 4 * g + (s & 3); }
+// 128-slot blocks (32x32x64 MFMA): the key behind byte jj of 16-byte half e of contraction step j in
+// lane half h -- where the accumulator of S^T = K Q^T left that key's weight
+__device__ __forceinline__ int key_of_slot_wide(int j, int e, int h, int jj) {
+    return 32 * (2 * j + e) + 8 * (jj >> 2) + 4 * h + (jj & 3);
+}
 
 // Quotient x/s prepared for the hardware's round-to-nearest-even conversion so that the final code
 // equals the rounding of the EXACT quotient: the correctly rounded float quotient can land exactly
@@ -78,12 +83,12 @@ template <int BS>
 __device__ __forceinline__ void write_v_block(const uint8_t* stage, uint4* dst, int tid) {
     if (BS == 128) {
         for (int c = tid; c < BS * 8; c += 256) {
-            const int lane = c & 63, h = (c >> 6) & 1, cb = c >> 7;
-            const int gg = lane >> 4, n = lane & 15;
-            union { uint4 v; uint8_t e[16]; } o;
+            const int lane = c & 63, e = (c >> 6) & 1, j = (c >> 7) & 1, db = c >> 8;
+            const int h = lane >> 5, n = lane & 31;
+            union { uint4 v; uint8_t b[16]; } o;
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj)
-                o.e[jj] = stage[key_of_slot_q(gg, 16 * h + jj) * 128 + 16 * cb + n];
+                o.b[jj] = stage[key_of_slot_wide(j, e, h, jj) * 128 + 32 * db + n];
             dst[c] = o.v;
         }
     } else {
@@ -155,8 +160,13 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint4* __rest
             if (role == FPS_ROLE_Q) {
                 dst[unit] = codes;
             } else if (role == FPS_ROLE_K) {
-                const int b = j >> 4, n = j & 15, gg = c16 >> 1, h = c16 & 1;
-                dst[(b * 2 + h) * 64 + gg * 16 + n] = codes;
+                if (BS == 128) {                     // 32x32x64 operand: lane 32h + n, k-step ks, 16-byte half e
+                    const int kb = j >> 5, n = j & 31, ks = c16 >> 2, h = (c16 >> 1) & 1, e = c16 & 1;
+                    dst[((kb * 2 + ks) * 2 + e) * 64 + 32 * h + n] = codes;
+                } else {
+                    const int b = j >> 4, n = j & 15, gg = c16 >> 1, h = c16 & 1;
+                    dst[(b * 2 + h) * 64 + gg * 16 + n] = codes;
+                }
             } else {
                 reinterpret_cast<uint4*>(stage)[unit] = codes;
             }
