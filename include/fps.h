@@ -208,7 +208,8 @@ int fps_debug_mfma_rate(int workgroups, int iters, float* sink, void* stream);
  * (Sec. 3.4 calls the kernel tensor-core bound; this measures what the chip allows).  The kernel
  * loops `iters` times over 8 groups, a group being one matrix instruction (matrix_kind 0:
  * v_mfma_f32_16x16x128_f8f6f4 on E4M3; 1: v_mfma_f32_16x16x32_bf16; 2: none;
- * 3: v_mfma_f32_32x32x64_f8f6f4 on E4M3, twice the work of 0) followed by
+ * 3: v_mfma_f32_32x32x64_f8f6f4 on E4M3, twice the work of 0; 4: v_mfma_f32_32x32x16_bf16, twice
+ * the work of 1) followed by
  * valu_per_mfma (one of 0 1 2 3 4 6 8 12 16 24 32) vector units (valu_kind 0: one v_fma_f32; 1: one
  * v_exp_f32 plus one v_add_f32), with no memory traffic.  `workgroups` workgroups of 256 threads
  * are launched, each reserving 1/workgroups_per_cu of a compute unit's LDS so that exactly that

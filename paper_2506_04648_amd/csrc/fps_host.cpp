@@ -328,8 +328,8 @@ int fps_debug_issue_mix(int matrix_kind, int valu_per_mfma, int valu_kind, int w
                         void* stream) {
     FPS_TRY(check_ptr(sink, "sink"));
     FPS_TRY(check_ptr(cycles, "cycles"));
-    if (matrix_kind < 0 || matrix_kind > 3 || valu_kind < 0 || valu_kind > 1) {
-        set_error("matrix_kind must be 0 (E4M3 16x16x128), 1 (bf16), 2 (none) or 3 (E4M3 32x32x64); valu_kind 0 (fma) or 1 (exp2)");
+    if (matrix_kind < 0 || matrix_kind > 4 || valu_kind < 0 || valu_kind > 1) {
+        set_error("matrix_kind must be 0 (E4M3 16x16x128), 1 (bf16 16x16x32), 2 (none), 3 (E4M3 32x32x64) or 4 (bf16 32x32x16); valu_kind 0 (fma) or 1 (exp2)");
         return FPS_ERR_INVALID_ARG;
     }
     if (workgroups_per_cu < 1 || workgroups_per_cu > 8) {

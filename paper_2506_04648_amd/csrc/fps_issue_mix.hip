@@ -12,13 +12,13 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
-enum { kMixFp8 = 0, kMixBf16 = 1, kMixNone = 2, kMixFp8Wide = 3 };
+enum { kMixFp8 = 0, kMixBf16 = 1, kMixNone = 2, kMixFp8Wide = 3, kMixBf16Wide = 4 };
 typedef float v16f __attribute__((ext_vector_type(16)));
 enum { kOpFma = 0, kOpExp = 1 };
 
 // KIND: the matrix instruction (v_mfma_f32_16x16x128_f8f6f4 with E4M3 operands, 8 passes;
-// v_mfma_f32_16x16x32_bf16, 4 passes; none; or v_mfma_f32_32x32x64_f8f6f4, 16 passes and twice
-// the work of the first).  NV v_fma_f32 per group.  Eight accumulator chains,
+// v_mfma_f32_16x16x32_bf16, 4 passes; none; v_mfma_f32_32x32x64_f8f6f4, 16 passes and twice the
+// work of the first; or v_mfma_f32_32x32x16_bf16, 8 passes and twice the work of the second).  NV v_fma_f32 per group.  Eight accumulator chains,
 // so a matrix instruction depends on the one issued eight groups earlier; every vector instruction
 // continues its own chain, one per group.  cycles[workgroup * 4 + wave] receives the wave's shader
 // clocks for the whole loop.
@@ -54,6 +54,8 @@ __global__ __launch_bounds__(256) void issue_mix_kernel(float* __restrict__ sink
                 c[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a16, b16, c[i], 0, 0, 0);
             else if (KIND == kMixFp8Wide)
                 cw[i & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, cw[i & 3], 0, 0, 0, 0, 0, 0);
+            else if (KIND == kMixBf16Wide)
+                cw[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a16, b16, cw[i & 3], 0, 0, 0);
 #pragma unroll
             for (int j = 0; j < NV; ++j) f[j] = __builtin_fmaf(f[j], k1, k2);
             __builtin_amdgcn_sched_barrier(0);              // groups stay as written
@@ -105,6 +107,8 @@ __global__ __launch_bounds__(256) void issue_mix_exp_kernel(float* __restrict__ 
                 c[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a16, b16, c[i], 0, 0, 0);
             else if (KIND == kMixFp8Wide)
                 cw[i & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, cw[i & 3], 0, 0, 0, 0, 0, 0);
+            else if (KIND == kMixBf16Wide)
+                cw[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a16, b16, cw[i & 3], 0, 0, 0);
 #pragma unroll
             for (int j = 0; j < NV; ++j) f[j] = __builtin_amdgcn_exp2f(f[j]) - 1.0f;   // stays in (-1, 0)
             __builtin_amdgcn_sched_barrier(0);
@@ -175,6 +179,7 @@ int launch_issue_mix(int kind, int nv, int op, int workgroups_per_cu, int workgr
     if (kind == kMixFp8)       e = launch_kind<kMixFp8>(nv, op, workgroups, lds, iters, sink, cycles, st, &known);
     else if (kind == kMixBf16) e = launch_kind<kMixBf16>(nv, op, workgroups, lds, iters, sink, cycles, st, &known);
     else if (kind == kMixFp8Wide) e = launch_kind<kMixFp8Wide>(nv, op, workgroups, lds, iters, sink, cycles, st, &known);
+    else if (kind == kMixBf16Wide) e = launch_kind<kMixBf16Wide>(nv, op, workgroups, lds, iters, sink, cycles, st, &known);
     else                       e = launch_kind<kMixNone>(nv, op, workgroups, lds, iters, sink, cycles, st, &known);
     if (!known) {
         set_error("valu_per_mfma must be one of 0 1 2 3 4 6 8 12 16 24 32");

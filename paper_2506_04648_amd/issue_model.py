@@ -6,7 +6,7 @@ from __future__ import annotations
 import sys
 
 NV = (0, 1, 2, 4, 6, 8, 12, 16, 24, 32)
-KINDS = ((0, "E4M3 16x16x128"), (3, "E4M3 32x32x64"), (1, "bf16 16x16x32"), (2, "no MFMA"))
+KINDS = ((0, "E4M3 16x16x128"), (3, "E4M3 32x32x64"), (1, "bf16 16x16x32"), (4, "bf16 32x32x16"), (2, "no MFMA"))
 
 
 def measure(kind, nv, op, per_cu, iters=2000, cus=256):

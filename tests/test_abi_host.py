@@ -159,7 +159,7 @@ def test_device_entry_points_validate_before_launching():
     assert L.fps_debug_mfma_rate(0, 4, good, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_mfma_rate(4, 0, good, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_mfma_rate(4, 4, None, None) == fps.FPS_ERR_INVALID_ARG
-    assert L.fps_debug_issue_mix(4, 0, 0, 1, 4, 4, good, good, None) == fps.FPS_ERR_INVALID_ARG
+    assert L.fps_debug_issue_mix(5, 0, 0, 1, 4, 4, good, good, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_issue_mix(0, 0, 2, 1, 4, 4, good, good, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_issue_mix(0, 0, 0, 9, 4, 4, good, good, None) == fps.FPS_ERR_INVALID_ARG
     assert L.fps_debug_issue_mix(0, 0, 0, 1, 4, 4, None, good, None) == fps.FPS_ERR_INVALID_ARG
