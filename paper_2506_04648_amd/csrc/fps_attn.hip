@@ -1354,6 +1354,245 @@ void attn_bf16_kernel(AttnArgs a, MaskTables) {
                    &lds[0][0] + wave * kStoreRegionBytes);
 }
 
+// ---------------------------------------------------------------------------------------------
+// BF16, 128-slot blocks: v_mfma_f32_32x32x16_bf16 / _f16 (8 passes, twice the work of a 16x16x32)
+// and the lane layout of attn_fp8_wide_kernel -- lane (n, h) holds query n, the keys
+// 8(r/4) + 4h + r%4 of a 32-key score block and the channels of the same pattern of a 32-channel
+// output block.  K and V are single-buffered as in attn_bf16_kernel (two barriers per iteration).
+// V's per-tile scale is a power of two here, so the PV product accumulates straight into O: a tile's
+// weight 2^E, E = log2(s^V) + m, is applied by keeping O relative to the largest E met so far --
+// O is rescaled (exactly) only when that grows, and a tile below it has the difference folded into
+// the exponent of its weights before they are rounded to fp16.
+// ---------------------------------------------------------------------------------------------
+template <bool MB, int NK>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_bf16_wide_kernel(AttnArgs a, MaskTables) {
+    constexpr int BS = 128;
+    constexpr int NTHR = 256;
+    constexpr int TILE_BYTES = BS * 256;
+    constexpr int CPT = (BS * 16) / NTHR;                  // 16-byte chunks per thread per operand tile (8)
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2][TILE_BYTES];   // K, V
+    const Geom& G = a.g;
+    const int KB = MB ? G.KB : 1;
+    const int KB_LAST = MB ? G.kb_last : 1;
+    const int KBS = MB ? G.KBS : 1;
+    const int NS = MB ? G.NS : 1;
+    int bh, u, jq;
+    if (!work_item(a, KB, &bh, &u, &jq)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, n = lane & 31;
+    const int uw = u % G.nW, uh = (u / G.nW) % G.nH, ut = u / (G.nW * G.nH);
+    if (MB && jq >= (ut == G.nT - 1 ? KB_LAST : KB)) {      // a query block of padding only
+        zero_block_rows<BS, NTHR>(a, bh, u, jq);
+        return;
+    }
+    const size_t tile0 = (size_t)bh * G.M;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(&lds[0][0]);
+
+    Bf16x8 qop[8];                                         // Q^T, contraction steps of 16 channels
+    float m_run = -INFINITY, l_run = 0.f;                  // row reference; sum of 2^14 P relative to it
+    float e_ref = 0.f;                                     // the largest weight exponent E met so far
+    float alpha_acc = 1.f;                                 // rescale owed to O before the delayed PV
+    v16f acc[4];
+    {
+        const int row = wave * 32 + n;
+        const uint4* p = reinterpret_cast<const uint4*>(a.q + (((tile0 + u) * KB + jq) * BS + row) * 256);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qop[ks].u = p[2 * ks + h];
+#pragma unroll
+        for (int db = 0; db < 4; ++db) acc[db] = zero16();
+    }
+    const float sc = kLog2eOverSqrtD;
+
+    TileWalk w0, w1;                                       // tile i and tile i+1
+    w0.init(a, KB, KB_LAST, KBS, ut, uh, uw);
+    w1 = w0;
+    w1.next();
+    const int ntiles = w0.n;
+    auto tile_of = [&](const TileWalk& w) FPS_INLINE { return (w.vt * G.nH + w.vh) * G.nW + w.vw; };
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    auto stage_chunk = [&](int buf, const uint8_t* src, int c) FPS_INLINE {
+        dma_chunk_of(c, src + wave_s * (CPT * 1024), lane * 16, lds_base + buf * TILE_BYTES + wave_s * (CPT * 1024));
+    };
+    auto k_blk = [&](const TileWalk& w) FPS_INLINE { return a.k + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
+    auto v_blk = [&](const TileWalk& w) FPS_INLINE { return a.v + ((tile0 + tile_of(w)) * KB + w.jk) * TILE_BYTES; };
+    const uint4* ldsK4 = reinterpret_cast<const uint4*>(lds[0]);
+    const uint4* ldsV4 = reinterpret_cast<const uint4*>(lds[1]);
+
+    v16f s[4];                                             // S^T, four blocks of 32 keys
+    Bf16x8 pop[8];                                         // P^T in fp16: contraction steps of 16 keys
+    Bf16x8 ring[4];                                        // MFMA operands on their way from LDS
+
+    auto mask_scores = [&](int cls, int js, int jb) FPS_INLINE {      // padded keys of a boundary tile: -inf
+        cls = __builtin_amdgcn_readfirstlane(cls);
+        if (!((a.partial_cls >> cls) & 1u)) return;
+        if (!MB) {
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                const uint32_t code = arg_pair_code(cls, kb);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    s[kb][r] = select_lanes(pair_lane_mask(code, r), s[kb][r], -INFINITY);
+            }
+        } else {
+            uint64_t bm[2];
+            block_ballots<BS>(G, cls, js, jb, lane, bm);
+            if ((bm[0] & bm[1]) == ~0ull) return;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                const uint32_t bits = (uint32_t)(bm[kb >> 1] >> (32 * (kb & 1))) >> (4 * h);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (!((bits >> (8 * (r >> 2) + (r & 3))) & 1u)) s[kb][r] = -INFINITY;
+            }
+        }
+    };
+    // operand j of the K block: key block j/8, contraction step j%8
+    auto k_operand = [&](int j) FPS_INLINE { return ldsK4[j * 64 + lane]; };
+    auto qk_step = [&](int j) FPS_INLINE {
+        const int kb = j >> 3, ks = j & 7;
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[j & 3].v, qop[ks].v, ks == 0 ? zero16() : s[kb], 0, 0, 0);
+    };
+    // PV instructions alternate between two channel blocks, so that consecutive ones do not depend
+    // on each other: instruction j -> channel block 2(j/16) + j%2, contraction step (j%16)/2
+    auto pv_db = [](int j) { return 2 * (j >> 4) + (j & 1); };
+    auto pv_kk = [](int j) { return (j & 15) >> 1; };
+    auto v_operand = [&](int j) FPS_INLINE { return ldsV4[(pv_db(j) * 8 + pv_kk(j)) * 64 + lane]; };
+    auto pv_step = [&](int j) FPS_INLINE {
+        acc[pv_db(j)] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ring[j & 3].h, pop[pv_kk(j)].h, acc[pv_db(j)], 0, 0, 0);
+    };
+
+    // prologue: K(0) staged, S(0) computed
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) stage_chunk(0, k_blk(w0), c);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        ring[j & 3].u = k_operand(j);
+        qk_step(j);
+    }
+    mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
+
+    auto iteration = [&](auto first_tag, auto last_tag) FPS_INLINE {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        constexpr bool LAST = decltype(last_tag)::value;
+        const int v = tile_of(w0);
+        const float svv = load_uniform(a.sv, (tile0 + v) * NS + w0.js);        // 2^e exactly
+        const float e_v = (float)((int)((__float_as_uint(svv) >> 23) & 0xFFu) - 127);
+        if (a.visited && bh == 0 && tid == 0 && jq == 0 && w0.jk == 0) a.visited[(size_t)u * G.M + v] = 1;
+        const uint8_t* ksrc = LAST ? nullptr : k_blk(w1);
+        const uint8_t* vsrc = v_blk(w0);
+        __syncthreads();                 // every wave has finished QK(i): the K buffer is free; V(i-1) visible
+
+        // ---- phase 1: row maximum of S(i)  |  delayed PV(i-1)  |  K(i+1) streams in ------------
+        if (!FIRST && __any(alpha_acc != 1.0f)) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db) acc[db] *= alpha_acc;
+        }
+        float mx = __builtin_fmaxf(__builtin_fmaxf(s[0][0], s[0][1]), __builtin_fmaxf(s[0][2], s[0][3]));
+        if (!FIRST) {
+#pragma unroll
+            for (int j = 0; j < 3; ++j) ring[j].u = v_operand(j);
+        }
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {                     // one MFMA and one max3 per step
+            if (!FIRST) {
+                if (j + 3 < 32) ring[(j + 3) & 3].u = v_operand(j + 3);
+                pv_step(j);
+            }
+            if (j >= 2) {
+                mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[j >> 3][2 * (j & 7)]), s[j >> 3][2 * (j & 7) + 1]);
+                asm volatile("" : "+v"(mx));
+            }
+            if (!LAST && (j & 1) == 0 && j < 2 * CPT) stage_chunk(0, ksrc, j >> 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mx = max_over_row_pair(mx);
+        const float m_new = __builtin_fmaxf(m_run, __builtin_ceilf(mx * sc));
+        const float alpha_l = fast_exp2(m_run - m_new);    // 0 on the first tile (m_run = -inf)
+        m_run = m_new;
+        const float e_new = e_v + m_new;
+        const float e_top = FIRST ? e_new : __builtin_fmaxf(e_ref, e_new);
+        alpha_acc = FIRST ? 1.0f : fast_exp2(e_ref - e_top);
+        // <= 0: this tile's weight relative to O's scale; 64 binades down every fp16 weight is zero
+        const float below = __builtin_fmaxf(e_new - e_top, -64.0f);
+        e_ref = e_top;
+        // 2^14 * 2^(S' - m) * 2^below: the factor 2^14 keeps small weights in fp16's normal range and
+        // cancels against the row sum, which is taken of the same values
+        const float cm = kFp16PScaleLog2 - m_new + below;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // K(i+1): this thread's share landed
+        __syncthreads();                 // every wave has finished PV(i-1): the V buffer is free; K(i+1) visible
+
+        // ---- phase 2: P(i) in fp16  |  early QK(i+1)  |  V(i) streams in -----------------------
+        // step (kb, ks): a pair of weights of score block kb beside the MFMA (kb - 1, ks) that
+        // refills the block whose weights were taken one block earlier
+        float rs = 0.f;
+        if (!LAST) {
+#pragma unroll
+            for (int j = 0; j < 3; ++j) ring[j].u = k_operand(j);
+        }
+#pragma unroll
+        for (int kb = 0; kb <= 4; ++kb) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const int j = (kb - 1) * 8 + ks;
+                if (!LAST && kb >= 1) {
+                    if (j + 3 < 32) ring[(j + 3) & 3].u = k_operand(j + 3);
+                    qk_step(j);
+                }
+                if (kb < 4) {
+                    const float p0 = fast_exp2(__builtin_fmaf(s[kb][2 * ks], sc, cm));
+                    const float p1 = fast_exp2(__builtin_fmaf(s[kb][2 * ks + 1], sc, cm));
+                    rs += p0;
+                    rs += p1;
+                    uint32_t wd = __builtin_bit_cast(uint32_t, __builtin_convertvector(v2f{p0, p1}, v2h));
+                    asm volatile("" : "+v"(wd), "+v"(rs));  // keep the pass in place
+                    reinterpret_cast<uint32_t*>(&pop[2 * kb + (ks >> 2)].u)[ks & 3] = wd;
+                }
+                if (kb * 8 + ks < CPT) stage_chunk(1, vsrc, kb * 8 + ks);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // the row sum was taken of weights scaled by 2^below
+        l_run = __builtin_fmaf(rs, fast_exp2(-below), l_run * alpha_l);
+        w0.next();
+        w1.next();
+        if (!LAST) mask_scores(tile_class(G, w0.vt, w0.vh, w0.vw), w0.js, w0.jb);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // V(i): this thread's share landed
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    if constexpr (NK == kOneKeyBlock) {
+        iteration(T_{}, T_{});
+    } else if constexpr (NK == kManyKeyBlocks) {
+        iteration(T_{}, F_{});
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{});
+        iteration(F_{}, T_{});
+    } else if (ntiles == 1) {
+        iteration(T_{}, T_{});
+    } else {
+        iteration(T_{}, F_{});
+        for (int it = 1; it + 1 < ntiles; ++it) iteration(F_{}, F_{});
+        iteration(F_{}, T_{});
+    }
+    // epilogue: the last tile's PV
+    __syncthreads();
+    if (__any(alpha_acc != 1.0f)) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db) acc[db] *= alpha_acc;
+    }
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        ring[j & 3].u = v_operand(j);
+        pv_step(j);
+    }
+    const float l = sum_over_row_pair(l_run);
+    const float inv = l > 0.f ? fast_exp2(e_ref - m_run) / l : 0.f;
+    __syncthreads();                                       // all waves are done with the staged tiles
+    store_rows_wide(a, bh, u, jq, KBS, tile_class(G, ut, uh, uw), wave, lane, acc, inv,
+                    &lds[0][0] + wave * kStoreRegionBytes);
+}
+
 // Debug: raw E4M3 score accumulators sum_c q_ic * k_jc of one tile pair, produced by the same MFMA
 // instruction and operand layouts as attn_fp8_kernel; out[i*BS + j], query-major.
 template <int BS>
@@ -1523,22 +1762,26 @@ int launch_attn(const Geom& g, const fps_window& win, int prec, const void* q, c
     } while (0)
 #define FPS_FP8_WIDE(VCH_, MB_, NK_) attn_fp8_wide_kernel<VCH_, MB_, NK_>
 #define FPS_FP8_SMALL(VCH_, MB_, NK_) attn_fp8_kernel<32, VCH_, MB_, NK_>
-#define FPS_LAUNCH_BF16(BS_, THREADS_)                                                             \
+#define FPS_LAUNCH_BF16(KERNEL_, THREADS_)                                                         \
     do {                                                                                           \
-        if (multi && many) attn_bf16_kernel<BS_, true, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
-        else if (multi) attn_bf16_kernel<BS_, true, kAnyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
-        else if (one) attn_bf16_kernel<BS_, false, kOneKeyBlock><<<grid, THREADS_, 0, st>>>(a, t);  \
-        else          attn_bf16_kernel<BS_, false, kManyKeyBlocks><<<grid, THREADS_, 0, st>>>(a, t); \
+        if (multi && many) KERNEL_(true, kManyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);         \
+        else if (multi) KERNEL_(true, kAnyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);             \
+        else if (one) KERNEL_(false, kOneKeyBlock)<<<grid, THREADS_, 0, st>>>(a, t);               \
+        else          KERNEL_(false, kManyKeyBlocks)<<<grid, THREADS_, 0, st>>>(a, t);             \
     } while (0)
+#define FPS_BF16_WIDE(MB_, NK_) attn_bf16_wide_kernel<MB_, NK_>
+#define FPS_BF16_SMALL(MB_, NK_) attn_bf16_kernel<32, MB_, NK_>
     if (prec == FPS_PREC_FP8) {
         if (g.BS == 128) FPS_LAUNCH_FP8(FPS_FP8_WIDE, 256); else FPS_LAUNCH_FP8(FPS_FP8_SMALL, 64);
     } else {
-        if (g.BS == 128) FPS_LAUNCH_BF16(128, 256); else FPS_LAUNCH_BF16(32, 64);
+        if (g.BS == 128) FPS_LAUNCH_BF16(FPS_BF16_WIDE, 256); else FPS_LAUNCH_BF16(FPS_BF16_SMALL, 64);
     }
 #undef FPS_LAUNCH_FP8
 #undef FPS_FP8_WIDE
 #undef FPS_FP8_SMALL
 #undef FPS_LAUNCH_BF16
+#undef FPS_BF16_WIDE
+#undef FPS_BF16_SMALL
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? FPS_OK : hip_fail(e, "attention launch");
 }

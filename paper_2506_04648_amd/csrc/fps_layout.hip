@@ -15,11 +15,16 @@
 //   Q : row-major [token][128]
 //   K : 16-byte chunk ((b*2 + h)*64 + lane) = K[16b + n][32g + 16h + 0..15]
 //   V :  8-byte chunk (cb*64 + lane), byte j = V[key(g,j)][16cb + n], key(g,s) = 16*(s/4) + 4g + s%4
-// BF16 (both block sizes), 16x16x32 instructions; lane = 16g + n:
+// BF16, BS = 128 -- operands of the 32x32x16 instructions; lane = 32h + n:
 //   Q : row-major [token][128]                                              (BS*256 bytes)
-//   K : 16-byte chunk ((b*4 + ks)*64 + lane) = K[16b + n][32ks + 8g + 0..7]
-//   V : 16-byte chunk ((kk*8 + cb)*64 + lane), element e -> V[32kk + key(g,e)][16cb + n],
+//   K : 16-byte chunk ((kb*8 + ks)*64 + lane) = K[32kb + n][16ks + 8h + 0..7]
+//   V : 16-byte chunk ((db*8 + kk)*64 + lane), element el = V[key][32db + n] with
+//       key = 32(kk/2) + 8(2(kk%2) + el/4) + 4h + el%4 (the key order of the 32x32 accumulator),
 //       stored as fp16 after an exact power-of-two scaling per scale group (see pack_bf16_kernel)
+// BF16, BS = 32 -- 16x16x32 instructions; lane = 16g + n:
+//   Q : row-major [token][128]
+//   K : 16-byte chunk ((b*4 + ks)*64 + lane) = K[16b + n][32ks + 8g + 0..7]
+//   V : 16-byte chunk ((kk*8 + cb)*64 + lane), element e -> V[32kk + key(g,e)][16cb + n], fp16 as above
 // key(g,s) is the key that slot s of lane group g holds after a 16x16 MFMA wrote S^T = K Q^T: the
 // accumulator of lane (n,g) for key block b has keys 16b + 4g + 0..3, so P^T can be fed back as
 // the second operand of the PV product without any cross-lane movement.
@@ -103,8 +108,13 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
     if (role == FPS_ROLE_K) {
         for (int c = threadIdx.x; c < kChunks; c += 256) {
             const int j = c >> 4, c8 = c & 15;             // row, 8-channel chunk
-            const int b = j >> 4, n = j & 15, ks = c8 >> 2, gg = c8 & 3;
-            dst[(b * 4 + ks) * 64 + gg * 16 + n] = load(c);
+            if (BS == 128) {                               // 32x32x16 operand: lane 32h + n, step ks
+                const int kb = j >> 5, n = j & 31, ks = c8 >> 1, h = c8 & 1;
+                dst[(kb * 8 + ks) * 64 + 32 * h + n] = load(c);
+            } else {
+                const int b = j >> 4, n = j & 15, ks = c8 >> 2, gg = c8 & 3;
+                dst[(b * 4 + ks) * 64 + gg * 16 + n] = load(c);
+            }
         }
         return;
     }
@@ -127,13 +137,23 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
     const float down = __uint_as_float((uint32_t)(127 - e) << 23);     // 2^-e
     if (!tile_amax && threadIdx.x == 0) vscale[blk] = __uint_as_float((uint32_t)(127 + e) << 23);
     for (int c = threadIdx.x; c < kChunks; c += 256) {
-        const int lane = c & 63, cb = (c >> 6) & 7, kk = c >> 9;
-        const int gg = lane >> 4, n = lane & 15;
+        const int lane = c & 63;
         union { uint4 v; _Float16 h[8]; } o;
+        if (BS == 128) {
+            const int kk = (c >> 6) & 7, db = c >> 9, hh = lane >> 5, n = lane & 31;
 #pragma unroll
-        for (int el = 0; el < 8; ++el) {
-            const uint32_t bits = tile[(32 * kk + key_of_slot(gg, el)) * 128 + 16 * cb + n];
-            o.h[el] = (_Float16)(__uint_as_float(bits << 16) * down);
+            for (int el = 0; el < 8; ++el) {
+                const int key = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (el >> 2)) + 4 * hh + (el & 3);
+                const uint32_t bits = tile[key * 128 + 32 * db + n];
+                o.h[el] = (_Float16)(__uint_as_float(bits << 16) * down);
+            }
+        } else {
+            const int cb = (c >> 6) & 7, kk = c >> 9, gg = lane >> 4, n = lane & 15;
+#pragma unroll
+            for (int el = 0; el < 8; ++el) {
+                const uint32_t bits = tile[(32 * kk + key_of_slot(gg, el)) * 128 + 16 * cb + n];
+                o.h[el] = (_Float16)(__uint_as_float(bits << 16) * down);
+            }
         }
         dst[c] = o.v;
     }
