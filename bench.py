@@ -147,6 +147,26 @@ def main():
     mfma_sustained = mfma_flop / (m0.elapsed_time(m1) * 1e-3) / 1e12
     del sink
 
+    # The same launch on all-zero operands: identical instruction stream, work items and memory
+    # traffic, but no switching activity in the matrix and vector data paths.  What it gains over the
+    # real data is the shader clock the chip's power management takes away under load.
+    zero_codes = torch.zeros_like(packed[0])
+    one_scales = torch.ones_like(scales[0])
+
+    def attn_zero():
+        fps.attn_fwd(shape, w.window, fps.PREC_FP8, zero_codes, zero_codes, zero_codes,
+                     one_scales, one_scales, one_scales, out=out_raster, raster_out=True)
+    for _ in range(3):
+        attn_zero()
+    z0, z1 = ev(), ev()
+    z0.record()
+    for _ in range(10):
+        attn_zero()
+    z1.record()
+    torch.cuda.synchronize()
+    attn_zero_ms = z0.elapsed_time(z1) / 10
+    del zero_codes, one_scales
+
     # bytes the three quantise launches really move: the un-padded bf16 raster read, the packed codes
     # (padded to whole tiles) and the scales written
     tokens = w.grid[0] * w.grid[1] * w.grid[2]
@@ -167,10 +187,11 @@ def main():
         "breakdown_median_ms": {"tile_order_quantize_x3": quant_med, "attention_raster_out": attn_med},
         "attention_tflops": flop / (attn_ms * 1e-3) / 1e12,
         "attention_tflops_real_tokens_only": useful_flop / (attn_ms * 1e-3) / 1e12,
+        "attention_ms_all_zero_operands": attn_zero_ms,
         "mfma_only_sustained_tflops": mfma_sustained,
         "attention_frac_of_sustained_mfma": flop / (attn_ms * 1e-3) / 1e12 / mfma_sustained,
         "quantize_GBps": quant_bytes / (quant_ms * 1e-3) / 1e9,
-        "roofline": {"bound": "mfma", "kernel": "attn_fp8_kernel", "achieved": flop / (attn_ms * 1e-3) / 1e12,
+        "roofline": {"bound": "mfma", "kernel": "attn_fp8_wide_kernel", "achieved": flop / (attn_ms * 1e-3) / 1e12,
                      "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop / (attn_ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
                      "traffic": traffic.get("bytes"), "traffic_range": traffic.get("range"),

@@ -1,13 +1,19 @@
 // Sliding-tile attention forward (Eq. 2-3, Sec. 3.2 aggregation; Algorithm 1 steps 4-5).
 //
-// One workgroup per (bh, query tile, block of BS = 128 or 32 query slots of the tile); wave w owns
-// query rows 32w..32w+31 of the block as two 16-row blocks.  The kernel walks the box of key tiles
-// given by Eq. 2 -- tile pairs outside the box are never scheduled -- block by block, staging each
-// K and V block through LDS.  A tile of at most BS tokens is one block; larger tiles, and tiles cut
-// into quantisation sub-tiles, are several blocks (kernels instantiated with MB = true).  Scores are produced
-// transposed, S^T = K Q^T, so that a lane's accumulator holds one query row and the keys
-// 16b + 4g + 0..3; after the softmax those registers are, unchanged, the second operand of the
-// PV product O^T = V^T P^T (see the packed layouts in fps_layout.hip).
+// One workgroup per (bh, query tile, block of BS = 128 or 32 query slots of the tile).  The kernel
+// walks the box of key tiles given by Eq. 2 -- tile pairs outside the box are never scheduled --
+// block by block, staging each K and V block through LDS.  A tile of at most BS tokens is one
+// block; larger tiles, and tiles cut into quantisation sub-tiles, are several blocks (kernels
+// instantiated with MB = true).  Scores are produced transposed, S^T = K Q^T, so that a lane's
+// accumulator holds one query row and a fixed set of keys; after the softmax those registers are,
+// unchanged, the second operand of the PV product O^T = V^T P^T (see the packed layouts in
+// fps_layout.hip).
+//
+// Four kernels share that plan.  128-slot blocks (any scale group of more than 96 tokens) run on
+// the 32x32 matrix instructions: attn_fp8_wide_kernel, attn_bf16_wide_kernel; a wave of 64 lanes owns
+// 32 query rows.  32-slot blocks (small tiles) run on the 16x16 instructions: attn_fp8_kernel<32>,
+// attn_bf16_kernel<32>; the single wave owns 32 query rows as two 16-row blocks.  The 16x16 kernels
+// are written for either block size but only instantiated for 32.
 //
 // Softmax is online in base 2 with an integer row reference m (ceil of the running row maximum):
 // P = 2^(S' - m) <= 1, rescaling by 2^(m_old - m_new) is exact, and the E4M3 rounding of 448*P
