@@ -684,6 +684,13 @@ __device__ __forceinline__ float sum_over_row_pair(float t) {
     const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+// x if bit `idx` of the lane's word `bits` is set, otherwise -inf: two vector instructions (a
+// sign-extended one-bit field, a bitwise select) and no compare, so a run of them needs no scalar
+// registers for compare results
+__device__ __forceinline__ float keep_if_bit(float x, uint32_t bits, int idx) {
+    const uint32_t m = (uint32_t)(-(int)((bits >> idx) & 1u));
+    return __uint_as_float((__float_as_uint(x) & m) | (0xFF800000u & ~m));
+}
 // pair_code[c][kb], bits 2r + h: set iff the key that lane half h holds in register r of score block
 // kb, slot 32kb + 8(r/4) + 4h + r%4 of a one-block tile of class c, is a real token
 __device__ __forceinline__ uint32_t arg_pair_code(int cls, int kb) {
@@ -865,8 +872,7 @@ void attn_fp8_wide_kernel(AttnArgs a, MaskTables) {
             for (int kb = 0; kb < 4; ++kb) {
                 const uint32_t bits = (uint32_t)(bm[kb >> 1] >> (32 * (kb & 1))) >> (4 * h);
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!((bits >> (8 * (r >> 2) + (r & 3))) & 1u)) s[kb][r] = -INFINITY;
+                for (int r = 0; r < 16; ++r) s[kb][r] = keep_if_bit(s[kb][r], bits, 8 * (r >> 2) + (r & 3));
             }
         }
     };
@@ -1447,8 +1453,7 @@ void attn_bf16_wide_kernel(AttnArgs a, MaskTables) {
             for (int kb = 0; kb < 4; ++kb) {
                 const uint32_t bits = (uint32_t)(bm[kb >> 1] >> (32 * (kb & 1))) >> (4 * h);
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!((bits >> (8 * (r >> 2) + (r & 3))) & 1u)) s[kb][r] = -INFINITY;
+                for (int r = 0; r < 16; ++r) s[kb][r] = keep_if_bit(s[kb][r], bits, 8 * (r >> 2) + (r & 3));
             }
         }
     };
