@@ -16,6 +16,10 @@ ACC_EPS = acs.ACC_EPS    # accumulation bound of the E4M3 matrix instruction (te
 # expected; they must stay rare, and the slack granted must stay small on average.
 MAX_FRACTION_BEYOND_PLAIN_BAR = 1e-2     # share of outputs with |err| > MAX_TOL * RMS
 MAX_SLACK_MEAN = 0.3                     # mean slack per output, in units of the RMS
+# Largest slack of a single output.  One open P code on a near one-hot row moves that row's output
+# by 1/16 of |v| / l-share; at an outlier channel of V (8 x 4.5 sigma) under a dense window, where
+# the output RMS is 0.06 sigma, that is some tens of RMS.  Observed: 9.3 (dense 720p), 5 (sparse).
+MAX_SLACK_MAX = 64.0
 MAX_MEAN_ERR_SMALL_SAMPLE = 4 * MEAN_TOL # un-slacked mean bar of a tiny sample with ambiguous P codes
 
 
@@ -244,6 +248,7 @@ def assert_parity(stats, label=""):
     assert stats["sel_max_excess"] <= MAX_TOL, (label, stats)
     assert stats["flips_outside_accepted_set"] == 0, (label, stats)
     assert stats["slack_mean"] <= MAX_SLACK_MEAN, (label, stats)
+    assert stats["slack_max"] <= MAX_SLACK_MAX, (label, stats)
     # In a case of a few thousand outputs a single tie flip on a peaked row (a legitimate
     # alternative result, inside the accepted set) moves the plain mean past 2e-3 and is a visible
     # share of the outputs; there the mean bar applies to the error beyond the slack, and the plain
