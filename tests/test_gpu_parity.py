@@ -208,6 +208,50 @@ def test_score_accumulation_error_model(tiny):
     assert worst <= gu.ACC_EPS
 
 
+def test_score_accumulation_bound_on_adversarial_codes():
+    """Code patterns chosen to stress the matrix instruction's adder: a product of 448*448 beside
+    127 products of 1*1 (the hardware drops the seven ones that share the large product's group of
+    eight: the error is 7, not 127), cancelling large products over a small residue, uniformly
+    random codes of the whole format, random powers of two over 15 binades.  All stay inside the
+    accumulation bound the accepted set is built on."""
+    say("adversarial codes")
+    vals = e4m3.decode(np.arange(256, dtype=np.uint8))
+    finite = vals[np.isfinite(vals)]
+    rng = np.random.default_rng(7)
+
+    def ratio(q, k, tile):
+        w = dataclasses.replace(synth.TINY, grid=tile, tile=tile, heads=1, window=(1, 1, 1), config_id=23)
+        run = gu.GpuRun(w, qkv=[a[None].astype(np.float32) for a in (q, k, np.zeros_like(q))])
+        run.quantize()
+        r, got, exact = gu.score_error_ratio(run, 0, 0, 0)
+        return r / gu.ACC_EPS, float(np.max(np.abs(got - exact)))
+
+    for tile in [(1, 8, 16), (2, 4, 4)]:                     # 128-slot and 32-slot blocks
+        shp = tile + (128,)
+        q = np.ones(shp)
+        q[..., 0] = 448.0
+        r, err = ratio(q, q.copy(), tile)
+        say(f"  {tile} one dominant product: {r:.3f} of the bound, |err| {err:g}")
+        assert r <= 1.0 and err <= 8.0
+        q, k = np.ones(shp), np.ones(shp)
+        q[..., 0] = q[..., 1] = k[..., 0] = 448.0
+        k[..., 1] = -448.0
+        r, err = ratio(q, k, tile)
+        say(f"  {tile} cancelling pair: {r:.3f} of the bound, |err| {err:g}")
+        assert r <= 1.0
+        q, k = rng.choice(finite, shp), rng.choice(finite, shp)
+        q[0, 0, 0, 0] = k[0, 0, 0, 0] = 448.0                # the tile scale is exactly 1
+        r, err = ratio(q, k, tile)
+        say(f"  {tile} uniformly random codes: {r:.3f} of the bound")
+        assert r <= 1.0
+        q = 2.0 ** rng.integers(-6, 9, shp) * rng.choice([-1.0, 1.0], shp)
+        k = 2.0 ** rng.integers(-6, 9, shp) * rng.choice([-1.0, 1.0], shp)
+        q[0, 0, 0, 0] = k[0, 0, 0, 0] = 448.0
+        r, err = ratio(q, k, tile)
+        say(f"  {tile} random powers of two: {r:.3f} of the bound")
+        assert r <= 1.0
+
+
 # ---- attention -------------------------------------------------------------------------------
 def test_attention_tiny_fp8_full(tiny):
     say("attention tiny fp8")
