@@ -225,12 +225,18 @@ def main():
         p16 = [fps.pack_tiles_bf16(shape, raster[i], i, raster=True) for i in range(3)]
         bf16_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_BF16, p16[0][0], p16[1][0], p16[2][0],
                                              sv=p16[2][1], out=out_tiled), 2)
-        del p16
+        # the same launch on all-zero operands (see attention_ms_all_zero_operands)
+        z16 = torch.zeros_like(p16[0][0])
+        one_sv = torch.ones_like(p16[2][1])
+        bf16_zero_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_BF16, z16, z16, z16, sv=one_sv,
+                                                  out=out_tiled), 2)
+        del p16, z16, one_sv
         fp8d_ms = timed(lambda: fps.attn_fwd(shape, dense_win, fps.PREC_FP8, packed[0], packed[1], packed[2],
                                              scales[0], scales[1], scales[2], out=out_tiled), 2)
         result["dense"] = {"window_tiles": list(dense_win), "tflop_per_call": dflop / 1e12,
                            "bf16_ms": bf16_ms, "bf16_tflops": dflop / bf16_ms / 1e9,
                            "bf16_frac_of_peak": dflop / bf16_ms / 1e9 / BF16_PEAK_TFLOPS,
+                           "bf16_ms_all_zero_operands": bf16_zero_ms,
                            "fp8_ms": fp8d_ms, "fp8_tflops": dflop / fp8d_ms / 1e9}
         result["speedup_vs_own_dense_bf16"] = {"attention_only": bf16_ms / attn_ms,
                                                "with_quantize": bf16_ms / (attn_ms + quant_ms)}
