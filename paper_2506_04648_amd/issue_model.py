@@ -9,7 +9,7 @@ NV = (0, 1, 2, 4, 6, 8, 12, 16, 24, 32)
 KINDS = ((0, "E4M3 16x16x128"), (3, "E4M3 32x32x64"), (1, "bf16 16x16x32"), (4, "bf16 32x32x16"), (2, "no MFMA"))
 
 
-def measure(kind, nv, op, per_cu, iters=2000, cus=256):
+def measure(kind, nv, op, per_cu, iters=2000, cus=256, per_wave=False):
     import torch
     from . import fps
     dev = torch.device("cuda:0")
@@ -22,6 +22,9 @@ def measure(kind, nv, op, per_cu, iters=2000, cus=256):
     fps.debug_issue_mix(kind, nv, op, per_cu, wgs, iters, sink, cyc)
     b.record()
     torch.cuda.synchronize()
+    if per_wave:
+        c = cyc.double() / (iters * 8)
+        return float(c.min()), float(c.median()), float(c.max())
     # All waves are resident from the start, and the SIMD serves the older of two waves first (the
     # younger one gets what is left), so single waves' counts say little: the longest count is the
     # launch's duration in shader clocks, and the SIMD spent it on per_cu waves' groups.
@@ -44,6 +47,9 @@ def main(argv=None):
                     row.append("%6.1f" % g)
                 print("%-15s %-3s waves/SIMD %d | n = %s : %s | %.2f GHz" %
                       (kname, opname, per_cu, " ".join("%d" % n for n in NV), " ".join(row), ghz), flush=True)
+    lo, med, hi = measure(0, 0, 0, 2, per_wave=True)
+    print("E4M3 16x16x128 alone, two waves per SIMD, clocks per instruction counted by single waves: "
+          "fastest %.1f, median %.1f, slowest %.1f (the older wave of a SIMD is served first)" % (lo, med, hi))
     return 0
 
 
